@@ -1,0 +1,181 @@
+/*
+ * lshmoe.h - C ABI of the MI355X (gfx950) LSH-MoE token compression library.
+ *
+ * The library implements the per-GPU work that LSH-MoE places around the MoE
+ * all-to-all (Section 3.2; Algorithm 1 in the appendix):
+ *
+ *   lshmoe_hash        cross-polytope LSH of every token            (Eq. 3)
+ *   lshmoe_compress    cluster each expert's tokens by bucket and
+ *                      replace every cluster by its centroid        (Alg. 1, the two nested loops)
+ *   lshmoe_decompress  give every token the expert output of its
+ *                      centroid plus the token's residual           (Eq. 4, Eq. 5)
+ *
+ * Notation: T tokens of dimension d; every token is routed to k distinct
+ * experts out of E (assignment a = t*k + j is token t's j-th expert, N = T*k
+ * assignments); L hash functions, each a real matrix R_l with r rows (so 2r
+ * buckets per hash and (2r)^L combined buckets); S clusters ("segments"), one
+ * per non-empty (expert, bucket) pair.
+ *
+ * Conventions for every entry point
+ *   - All array pointers are DEVICE pointers owned by the caller, row-major,
+ *     contiguous, 16-byte aligned.  Inputs are never written; outputs must not
+ *     overlap inputs or each other.  The library keeps no pointer after a call
+ *     returns and allocates no device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it and return; nothing synchronises the host.
+ *     That is why the cluster count S stays in device memory and outputs are
+ *     sized for the worst case S == N.
+ *   - dtype LSHMOE_F32 is IEEE binary32; LSHMOE_BF16 is bfloat16 (upper 16 bits
+ *     of binary32).  All sums are accumulated in binary32 and rounded to the
+ *     storage type once, round-to-nearest-even.
+ *   - The row size d * sizeof(element) must be a multiple of 16 bytes.
+ *   - Return value: LSHMOE_OK or an error code; nothing is enqueued on a host
+ *     side error.  lshmoe_last_error() gives a thread-local description.
+ *     Arguments are checked on the host before any GPU call, so the checks
+ *     behave the same on a machine without a GPU.
+ *   - Preconditions that are NOT checked (results are unspecified, memory
+ *     safety is kept for out-of-range expert ids): finite inputs;
+ *     0 <= expert[t][j] < E; the k experts of one token are distinct.
+ */
+#ifndef LSHMOE_H
+#define LSHMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LSHMOE_OK = 0,
+  LSHMOE_ERR_NULL = 1,        /* a required pointer is NULL                         */
+  LSHMOE_ERR_SHAPE = 2,       /* a size is non-positive or inconsistent (k > E ...) */
+  LSHMOE_ERR_UNSUPPORTED = 3, /* valid but outside what the kernels handle          */
+  LSHMOE_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small         */
+  LSHMOE_ERR_HIP = 5          /* a HIP runtime call failed                          */
+} lshmoe_status;
+
+typedef enum { LSHMOE_F32 = 0, LSHMOE_BF16 = 1 } lshmoe_dtype;
+
+/* Flags of lshmoe_decompress. */
+enum {
+  /* Drop the residual term: Y = E(centroid).  The paper's "without error
+   * compensation" arm (Section 4.2, Fig. 5). */
+  LSHMOE_FLAG_NO_RESIDUAL = 1u
+};
+
+/* Static, never-freed name of a status code. */
+const char* lshmoe_status_string(int status);
+
+/* Description of the last error raised on the calling thread ("" if none).
+ * Valid until the next library call on that thread. */
+const char* lshmoe_last_error(void);
+
+/* ABI version of this header (bumped when a signature changes). */
+int lshmoe_abi_version(void);
+
+/*
+ * Bytes of device scratch lshmoe_compress needs for these sizes (host only,
+ * touches no GPU).  Errors: NULL out_bytes; non-positive sizes; k > E;
+ * unsupported sizes as for lshmoe_compress.
+ */
+lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E,
+                                     int32_t L, int32_t r, lshmoe_dtype dtype,
+                                     size_t* out_bytes);
+
+/*
+ * Cross-polytope hash (Section 3.2, Eq. 3).  For hash l the token x is mapped
+ * to y = R_l x (r coordinates) and then to the nearest vertex of the
+ * cross-polytope {+-e_i}: code_l = i* if y[i*] >= 0 else i* + r, where i* is
+ * the lowest index attaining max_i |y_i|.  The L codes are the digits of a
+ * base-2r number, hash 0 most significant:
+ *     bucket[t] = ((code_0 * 2r + code_1) * 2r + ...) * 2r + code_{L-1}.
+ * R_l may be any real r x d matrix (a rotation restricted to r rows is the
+ * intended use; orthonormality is not required or checked).
+ *
+ *   tokens [T, d]   in   dtype
+ *   rot    [L, r, d] in  dtype
+ *   bucket [T]      out  uint64
+ *
+ * The products are exact in binary32 for bf16 inputs and are accumulated in
+ * binary32, so a token whose two largest |y_i| differ by less than about 1e-5
+ * relative may land on the other of the two vertices than exact arithmetic
+ * gives.
+ * Errors: NULL pointer; T, d, L, r <= 0; r < 2 or (2r)^L >= 2^63
+ * (UNSUPPORTED); r > 256 (UNSUPPORTED); d*sizeof(element) not a multiple of 16
+ * (UNSUPPORTED); launch failure (HIP).
+ */
+lshmoe_status lshmoe_hash(const void* tokens, const void* rot,
+                          int64_t T, int32_t d, int32_t L, int32_t r, lshmoe_dtype dtype,
+                          uint64_t* bucket, void* stream);
+
+/*
+ * Cluster and average (Algorithm 1: dispatch by expert, split each expert's
+ * tokens into clusters by bucket, take each cluster's mean; centroid formula
+ * of Section 2.3 with 1/n_j).
+ *
+ * Assignment a = t*k + j has key (expert[t][j], bucket[t]).  Clusters are the
+ * sets of assignments with equal key, numbered 0..S-1 by ascending
+ * (expert, bucket); inside a cluster members are ordered by ascending a.
+ *
+ *   tokens         [T, d]  in   dtype
+ *   expert         [T, k]  in   int32
+ *   bucket         [T]     in   uint64, every value < (2r)^L
+ *   centroids      [N, d]  out  dtype; rows 0..S-1 are written: the a2a payload
+ *   seg_offsets    [N+1]   out  int32; entries 0..S: cluster s owns perm[seg_offsets[s] .. seg_offsets[s+1])
+ *   seg_expert     [N]     out  int32; entries 0..S-1: destination expert of cluster s
+ *   expert_offsets [E+1]   out  int32; clusters of expert e are [expert_offsets[e], expert_offsets[e+1]):
+ *                               the per-destination send counts of the all-to-all
+ *   perm           [N]     out  int32; sorted position -> assignment
+ *   seg_of         [N]     out  int32; assignment -> cluster
+ *   num_segments   [1]     out  int32 (device); S
+ *   workspace              scratch of at least lshmoe_workspace_bytes(...) bytes, 256-byte aligned;
+ *                          contents on entry are ignored and on return are unspecified
+ *
+ * L and r only bound the bucket ids (they fix how many key bits are sorted).
+ * All integer outputs are deterministic; centroid sums run in member order, so
+ * the floating-point result is reproducible bit for bit.
+ * Errors: NULL pointer; T, d, k, E, L, r <= 0; k > E; N = T*k >= 2^30
+ * (UNSUPPORTED); (2r)^L >= 2^63 or bits(E-1) + bits((2r)^L - 1) > 64
+ * (UNSUPPORTED); row size not a multiple of 16 bytes (UNSUPPORTED); workspace
+ * too small or misaligned (WORKSPACE); launch failure (HIP).
+ */
+lshmoe_status lshmoe_compress(const void* tokens, const int32_t* expert, const uint64_t* bucket,
+                              int64_t T, int32_t d, int32_t k, int32_t E,
+                              int32_t L, int32_t r, lshmoe_dtype dtype,
+                              void* centroids, int32_t* seg_offsets, int32_t* seg_expert,
+                              int32_t* expert_offsets, int32_t* perm, int32_t* seg_of,
+                              int32_t* num_segments,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Restore with residual compensation (Eq. 4 and Eq. 5; last loop of
+ * Algorithm 1).  For every assignment a with s = seg_of[a]:
+ *     out[a, :] = expert_out[s, :] + (tokens[a / k, :] - centroids[s, :])
+ * evaluated in binary32 and rounded once.  The residual is taken against the
+ * stored centroid, so a one-member cluster returns expert_out[s] exactly.
+ * With LSHMOE_FLAG_NO_RESIDUAL: out[a, :] = expert_out[s, :].
+ *
+ *   tokens      [T, d]  in   dtype
+ *   centroids   [S, d]  in   dtype (as written by lshmoe_compress)
+ *   expert_out  [S, d]  in   dtype; E applied to each centroid row, same row order
+ *   seg_of      [N]     in   int32, as written by lshmoe_compress
+ *   seg_offsets [S+1]   in   int32 or NULL.  When given, one-member clusters skip
+ *                            the token and centroid reads (their difference is
+ *                            exactly zero); the result is the same either way.
+ *   out         [T, k, d] out dtype, assignment order
+ *
+ * Errors: NULL pointer (seg_offsets excepted); T, d, k <= 0; N >= 2^30
+ * (UNSUPPORTED); unknown flag bits (UNSUPPORTED); row size not a multiple of
+ * 16 bytes (UNSUPPORTED); launch failure (HIP).
+ */
+lshmoe_status lshmoe_decompress(const void* tokens, const void* centroids, const void* expert_out,
+                                const int32_t* seg_of, const int32_t* seg_offsets,
+                                int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, uint32_t flags,
+                                void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSHMOE_H */

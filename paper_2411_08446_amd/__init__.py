@@ -1,0 +1,12 @@
+"""MI355X-native LSH-MoE token compression path (hash -> compress -> decompress).
+
+The work is done by hand-written gfx950 HIP kernels in ``lib/liblshmoe.so``
+(built from ``csrc/`` by ``python -m paper_2411_08446_amd.build``); this package
+is the thin ctypes binding over the library's C ABI (``include/lshmoe.h``).
+"""
+from .binding import (  # noqa: F401
+    LIB_PATH, LshmoeError, CompressOutputs, load_library,
+    lshmoe_hash, lshmoe_compress, lshmoe_decompress, lshmoe_workspace_bytes,
+    LSHMOE_OK, LSHMOE_ERR_NULL, LSHMOE_ERR_SHAPE, LSHMOE_ERR_UNSUPPORTED, LSHMOE_ERR_WORKSPACE, LSHMOE_ERR_HIP,
+    LSHMOE_F32, LSHMOE_BF16, LSHMOE_FLAG_NO_RESIDUAL,
+)

@@ -1,0 +1,173 @@
+"""ctypes binding of ``liblshmoe.so``: same names as the C ABI, argument
+marshalling only.  Tensors are torch CUDA(ROCm) tensors used purely as device
+memory; every step of the path runs in the library's HIP kernels.  There is no
+fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "lib", "liblshmoe.so")
+
+LSHMOE_OK = 0
+LSHMOE_ERR_NULL = 1
+LSHMOE_ERR_SHAPE = 2
+LSHMOE_ERR_UNSUPPORTED = 3
+LSHMOE_ERR_WORKSPACE = 4
+LSHMOE_ERR_HIP = 5
+LSHMOE_F32 = 0
+LSHMOE_BF16 = 1
+LSHMOE_FLAG_NO_RESIDUAL = 1
+
+
+class LshmoeError(RuntimeError):
+    def __init__(self, status: int, name: str, detail: str):
+        super().__init__("%s: %s" % (name, detail))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
+    """Load the shared library (once) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(path):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_2411_08446_amd.build` "
+            "(there is no non-HIP fallback)" % path)
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, u32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32
+    lib.lshmoe_status_string.restype = ctypes.c_char_p
+    lib.lshmoe_status_string.argtypes = [ctypes.c_int]
+    lib.lshmoe_last_error.restype = ctypes.c_char_p
+    lib.lshmoe_last_error.argtypes = []
+    lib.lshmoe_abi_version.restype = ctypes.c_int
+    lib.lshmoe_abi_version.argtypes = []
+    lib.lshmoe_workspace_bytes.restype = ctypes.c_int
+    lib.lshmoe_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.lshmoe_hash.restype = ctypes.c_int
+    lib.lshmoe_hash.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, vp, vp]
+    lib.lshmoe_compress.restype = ctypes.c_int
+    lib.lshmoe_compress.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_int,
+                                    vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.lshmoe_decompress.restype = ctypes.c_int
+    lib.lshmoe_decompress.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != LSHMOE_OK:
+        lib = load_library()
+        raise LshmoeError(status, lib.lshmoe_status_string(status).decode(), lib.lshmoe_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LSHMOE_F32
+    if t.dtype == torch.bfloat16:
+        return LSHMOE_BF16
+    raise TypeError("tokens must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _ptr(t, dtype=None) -> int:
+    if t is None:
+        return 0
+    if not t.is_cuda:
+        raise ValueError("the library takes device pointers; got a %s tensor" % t.device)
+    if not t.is_contiguous():
+        raise ValueError("tensors must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("expected %s, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def lshmoe_workspace_bytes(T: int, d: int, k: int, E: int, L: int, r: int, dtype_code: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().lshmoe_workspace_bytes(T, d, k, E, L, r, dtype_code, ctypes.byref(out)))
+    return int(out.value)
+
+
+def lshmoe_hash(tokens: torch.Tensor, rot: torch.Tensor, bucket: torch.Tensor, stream=None) -> None:
+    """tokens [T, d], rot [L, r, d] (same dtype) -> bucket [T] (int64 tensor holding uint64 ids)."""
+    T, d = tokens.shape
+    L, r, d2 = rot.shape
+    if d2 != d or rot.dtype != tokens.dtype or bucket.numel() != T:
+        raise ValueError("shape/dtype mismatch between tokens, rot and bucket")
+    _check(load_library().lshmoe_hash(_ptr(tokens), _ptr(rot), T, d, L, r, _dtype_code(tokens),
+                                      _ptr(bucket, torch.int64), _stream(stream)))
+
+
+@dataclass
+class CompressOutputs:
+    """Caller-owned device buffers of lshmoe_compress, sized for S == N."""
+    centroids: torch.Tensor       # [N, d]
+    seg_offsets: torch.Tensor     # [N + 1] int32
+    seg_expert: torch.Tensor      # [N] int32
+    expert_offsets: torch.Tensor  # [E + 1] int32
+    perm: torch.Tensor            # [N] int32
+    seg_of: torch.Tensor          # [N] int32
+    num_segments: torch.Tensor    # [1] int32
+    workspace: torch.Tensor       # uint8
+
+    @staticmethod
+    def allocate(T: int, d: int, k: int, E: int, L: int, r: int, dtype: torch.dtype, device="cuda") -> "CompressOutputs":
+        N = T * k
+        code = LSHMOE_F32 if dtype == torch.float32 else LSHMOE_BF16
+        i32 = dict(dtype=torch.int32, device=device)
+        ws = lshmoe_workspace_bytes(T, d, k, E, L, r, code)
+        return CompressOutputs(
+            centroids=torch.empty((N, d), dtype=dtype, device=device),
+            seg_offsets=torch.empty(N + 1, **i32), seg_expert=torch.empty(N, **i32),
+            expert_offsets=torch.empty(E + 1, **i32), perm=torch.empty(N, **i32), seg_of=torch.empty(N, **i32),
+            num_segments=torch.empty(1, **i32),
+            workspace=torch.empty(ws + 256, dtype=torch.uint8, device=device))
+
+
+def _aligned_ws(ws: torch.Tensor):
+    base = ws.data_ptr()
+    pad = (-base) % 256
+    return base + pad, ws.numel() - pad
+
+
+def lshmoe_compress(tokens: torch.Tensor, expert: torch.Tensor, bucket: torch.Tensor, E: int, L: int, r: int,
+                    out: CompressOutputs, stream=None) -> None:
+    T, d = tokens.shape
+    k = expert.shape[1]
+    if expert.shape[0] != T or bucket.numel() != T:
+        raise ValueError("expert must be [T, k] and bucket [T]")
+    N = T * k
+    if (out.centroids.shape != (N, d) or out.centroids.dtype != tokens.dtype or out.seg_offsets.numel() != N + 1
+            or out.seg_expert.numel() != N or out.expert_offsets.numel() != E + 1 or out.perm.numel() != N
+            or out.seg_of.numel() != N or out.num_segments.numel() != 1):
+        raise ValueError("output buffers do not match T, k, d, E")
+    ws_ptr, ws_bytes = _aligned_ws(out.workspace)
+    i32 = torch.int32
+    _check(load_library().lshmoe_compress(
+        _ptr(tokens), _ptr(expert, i32), _ptr(bucket, torch.int64), T, d, k, E, L, r, _dtype_code(tokens),
+        _ptr(out.centroids), _ptr(out.seg_offsets, i32), _ptr(out.seg_expert, i32), _ptr(out.expert_offsets, i32),
+        _ptr(out.perm, i32), _ptr(out.seg_of, i32), _ptr(out.num_segments, i32), ws_ptr, ws_bytes, _stream(stream)))
+
+
+def lshmoe_decompress(tokens: torch.Tensor, centroids: torch.Tensor, expert_out: torch.Tensor, seg_of: torch.Tensor,
+                      seg_offsets, k: int, out: torch.Tensor, flags: int = 0, stream=None) -> None:
+    T, d = tokens.shape
+    if out.numel() != T * k * d or out.dtype != tokens.dtype or seg_of.numel() != T * k:
+        raise ValueError("out must hold [T, k, d] elements of the token dtype and seg_of N entries")
+    if centroids.dtype != tokens.dtype or expert_out.dtype != tokens.dtype:
+        raise TypeError("centroids and expert_out must have the token dtype")
+    _check(load_library().lshmoe_decompress(
+        _ptr(tokens), _ptr(centroids), _ptr(expert_out), _ptr(seg_of, torch.int32),
+        _ptr(seg_offsets, torch.int32), T, d, k, _dtype_code(tokens), flags, _ptr(out), _stream(stream)))

@@ -1,0 +1,160 @@
+// C ABI of the library: argument checks on the host, then kernel launches.
+// Every check runs before the first HIP call, so bad arguments are reported
+// the same way on a machine without a GPU.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "../../include/lshmoe.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+lshmoe_status fail(lshmoe_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+lshmoe_status ok() {
+  g_err[0] = '\0';
+  return LSHMOE_OK;
+}
+
+lshmoe_status hip_fail(const char* what, hipError_t e) {
+  return fail(LSHMOE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool dtype_ok(int dt) { return dt == LSHMOE_F32 || dt == LSHMOE_BF16; }
+size_t item_size(int dt) { return dt == LSHMOE_BF16 ? 2 : 4; }
+
+// (2r)^L < 2^63 ?
+bool bucket_space_ok(int L, int r) {
+  unsigned __int128 nb = 1;
+  for (int l = 0; l < L; ++l) {
+    nb *= (unsigned __int128)(2 * (uint64_t)r);
+    if (nb >= ((unsigned __int128)1 << 63)) return false;
+  }
+  return true;
+}
+
+constexpr int64_t kMaxAssignments = (int64_t)1 << 30;
+
+lshmoe_status check_row(int d, int dt) {
+  if (!dtype_ok(dt)) return fail(LSHMOE_ERR_UNSUPPORTED, "unknown dtype %d", dt);
+  if (((size_t)d * item_size(dt)) % 16 != 0)
+    return fail(LSHMOE_ERR_UNSUPPORTED, "row size d*sizeof(element) = %zu bytes is not a multiple of 16",
+                (size_t)d * item_size(dt));
+  return LSHMOE_OK;
+}
+
+lshmoe_status check_hash_params(int L, int r) {
+  if (L <= 0 || r <= 0) return fail(LSHMOE_ERR_SHAPE, "L and r must be positive (L=%d, r=%d)", L, r);
+  if (r < 2) return fail(LSHMOE_ERR_UNSUPPORTED, "r must be at least 2 (r=%d)", r);
+  if (!bucket_space_ok(L, r)) return fail(LSHMOE_ERR_UNSUPPORTED, "(2r)^L does not fit below 2^63 (L=%d, r=%d)", L, r);
+  return LSHMOE_OK;
+}
+
+lshmoe_status check_compress_shape(int64_t T, int d, int k, int E, int L, int r, int dt, lshmoe::GroupPlan* plan) {
+  if (T <= 0 || d <= 0 || k <= 0 || E <= 0)
+    return fail(LSHMOE_ERR_SHAPE, "T, d, k, E must be positive (T=%lld, d=%d, k=%d, E=%d)", (long long)T, d, k, E);
+  if (k > E) return fail(LSHMOE_ERR_SHAPE, "k=%d experts per token exceeds E=%d experts", k, E);
+  if (lshmoe_status st = check_hash_params(L, r)) return st;
+  if (lshmoe_status st = check_row(d, dt)) return st;
+  if (T >= kMaxAssignments || T * (int64_t)k >= kMaxAssignments)
+    return fail(LSHMOE_ERR_UNSUPPORTED, "N = T*k = %lld assignments; the limit is 2^30 - 1", (long long)(T * (int64_t)k));
+  if ((uint64_t)T * (uint64_t)k * ((size_t)d * item_size(dt) / 16) > 0xffffff00ull)
+    return fail(LSHMOE_ERR_UNSUPPORTED, "N*d is too large for one launch");
+  if (!lshmoe::plan_group(T, k, E, L, r, plan))
+    return fail(LSHMOE_ERR_UNSUPPORTED, "expert bits + bucket bits exceed 64 (E=%d, L=%d, r=%d)", E, L, r);
+  return LSHMOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lshmoe_status_string(int status) {
+  switch (status) {
+    case LSHMOE_OK: return "LSHMOE_OK";
+    case LSHMOE_ERR_NULL: return "LSHMOE_ERR_NULL";
+    case LSHMOE_ERR_SHAPE: return "LSHMOE_ERR_SHAPE";
+    case LSHMOE_ERR_UNSUPPORTED: return "LSHMOE_ERR_UNSUPPORTED";
+    case LSHMOE_ERR_WORKSPACE: return "LSHMOE_ERR_WORKSPACE";
+    case LSHMOE_ERR_HIP: return "LSHMOE_ERR_HIP";
+    default: return "LSHMOE_ERR_UNKNOWN";
+  }
+}
+
+const char* lshmoe_last_error(void) { return g_err; }
+
+int lshmoe_abi_version(void) { return 1; }
+
+lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E, int32_t L, int32_t r,
+                                     lshmoe_dtype dtype, size_t* out_bytes) {
+  if (!out_bytes) return fail(LSHMOE_ERR_NULL, "out_bytes is NULL");
+  lshmoe::GroupPlan plan;
+  if (lshmoe_status st = check_compress_shape(T, d, k, E, L, r, (int)dtype, &plan)) return st;
+  *out_bytes = plan.total_bytes;
+  return ok();
+}
+
+lshmoe_status lshmoe_hash(const void* tokens, const void* rot, int64_t T, int32_t d, int32_t L, int32_t r,
+                          lshmoe_dtype dtype, uint64_t* bucket, void* stream) {
+  if (!tokens || !rot || !bucket) return fail(LSHMOE_ERR_NULL, "tokens, rot and bucket must be non-NULL");
+  if (T <= 0 || d <= 0) return fail(LSHMOE_ERR_SHAPE, "T and d must be positive (T=%lld, d=%d)", (long long)T, d);
+  if (lshmoe_status st = check_hash_params(L, r)) return st;
+  if (lshmoe_status st = check_row(d, (int)dtype)) return st;
+  if (T >= kMaxAssignments) return fail(LSHMOE_ERR_UNSUPPORTED, "T = %lld tokens; the limit is 2^30 - 1", (long long)T);
+  if (r > 256) return fail(LSHMOE_ERR_UNSUPPORTED, "r = %d rotated dimensions per hash; the limit is 256", r);
+  hipError_t e = lshmoe::launch_hash(tokens, rot, T, d, L, r, dtype == LSHMOE_BF16, bucket, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("hash launch", e);
+  return ok();
+}
+
+lshmoe_status lshmoe_compress(const void* tokens, const int32_t* expert, const uint64_t* bucket, int64_t T, int32_t d,
+                              int32_t k, int32_t E, int32_t L, int32_t r, lshmoe_dtype dtype, void* centroids,
+                              int32_t* seg_offsets, int32_t* seg_expert, int32_t* expert_offsets, int32_t* perm,
+                              int32_t* seg_of, int32_t* num_segments, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  if (!tokens || !expert || !bucket || !centroids || !seg_offsets || !seg_expert || !expert_offsets || !perm ||
+      !seg_of || !num_segments)
+    return fail(LSHMOE_ERR_NULL, "an input or output pointer is NULL");
+  lshmoe::GroupPlan plan;
+  if (lshmoe_status st = check_compress_shape(T, d, k, E, L, r, (int)dtype, &plan)) return st;
+  if (!workspace) return fail(LSHMOE_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", plan.total_bytes);
+  if (((uintptr_t)workspace & 255u) != 0) return fail(LSHMOE_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < plan.total_bytes)
+    return fail(LSHMOE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.total_bytes);
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = lshmoe::launch_group(plan, expert, bucket, k, E, seg_offsets, seg_expert, expert_offsets, perm, seg_of,
+                                      num_segments, (char*)workspace, s);
+  if (e != hipSuccess) return hip_fail("group launch", e);
+  e = lshmoe::launch_centroid(tokens, perm, seg_offsets, num_segments, centroids, plan.N, k, d, dtype == LSHMOE_BF16, s);
+  if (e != hipSuccess) return hip_fail("centroid launch", e);
+  return ok();
+}
+
+lshmoe_status lshmoe_decompress(const void* tokens, const void* centroids, const void* expert_out,
+                                const int32_t* seg_of, const int32_t* seg_offsets, int64_t T, int32_t d, int32_t k,
+                                lshmoe_dtype dtype, uint32_t flags, void* out, void* stream) {
+  if (!tokens || !centroids || !expert_out || !seg_of || !out)
+    return fail(LSHMOE_ERR_NULL, "an input or output pointer is NULL");
+  if (T <= 0 || d <= 0 || k <= 0)
+    return fail(LSHMOE_ERR_SHAPE, "T, d, k must be positive (T=%lld, d=%d, k=%d)", (long long)T, d, k);
+  if (lshmoe_status st = check_row(d, (int)dtype)) return st;
+  if (flags & ~(uint32_t)LSHMOE_FLAG_NO_RESIDUAL) return fail(LSHMOE_ERR_UNSUPPORTED, "unknown flag bits 0x%x", flags);
+  if (T >= kMaxAssignments || T * (int64_t)k >= kMaxAssignments)
+    return fail(LSHMOE_ERR_UNSUPPORTED, "N = T*k = %lld assignments; the limit is 2^30 - 1", (long long)(T * (int64_t)k));
+  if ((uint64_t)T * (uint64_t)k * ((size_t)d * item_size((int)dtype) / 16) > 0xffffff00ull)
+    return fail(LSHMOE_ERR_UNSUPPORTED, "N*d is too large for one launch");
+  hipError_t e = lshmoe::launch_restore(tokens, centroids, expert_out, seg_of, seg_offsets, out, T * (int64_t)k, k, d,
+                                        dtype == LSHMOE_BF16, flags, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("restore launch", e);
+  return ok();
+}
+
+}  // extern "C"

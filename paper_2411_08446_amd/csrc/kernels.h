@@ -1,0 +1,46 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "common.h"
+
+namespace lshmoe {
+
+// ---- step 1: hash -------------------------------------------------------
+hipError_t launch_hash(const void* tokens, const void* rot, int64_t T, int d, int L, int r, bool bf16,
+                       uint64_t* bucket, hipStream_t stream);
+
+// ---- step 2: group ------------------------------------------------------
+struct GroupPlan {
+  int64_t N;
+  int ebits, bbits;      // key = expert << bbits | bucket
+  int passes;            // 8-bit radix passes over ebits + bbits key bits
+  uint32_t sort_blocks;  // tiles of kSortTile assignments
+  uint32_t seg_blocks;   // tiles of kSegTile sorted positions
+  // byte offsets into the workspace
+  size_t off_key[2], off_idx[2], off_hist, off_blocksum, total_bytes;
+};
+constexpr int kSortTile = 2048;
+constexpr int kSegTile = 1024;
+
+// Fills the plan; returns false when ebits + bbits > 64.
+bool plan_group(int64_t T, int k, int E, int L, int r, GroupPlan* plan);
+
+hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint64_t* bucket, int k, int E,
+                        int32_t* seg_offsets, int32_t* seg_expert, int32_t* expert_offsets, int32_t* perm,
+                        int32_t* seg_of, int32_t* num_segments, char* workspace, hipStream_t stream);
+
+// ---- step 3: centroid ---------------------------------------------------
+hipError_t launch_centroid(const void* tokens, const int32_t* perm, const int32_t* seg_offsets,
+                           const int32_t* num_segments, void* centroids, int64_t N, int k, int d, bool bf16,
+                           hipStream_t stream);
+
+// ---- step 4: restore ----------------------------------------------------
+hipError_t launch_restore(const void* tokens, const void* centroids, const void* expert_out,
+                          const int32_t* seg_of, const int32_t* seg_offsets, void* out, int64_t N, int k, int d,
+                          bool bf16, uint32_t flags, hipStream_t stream);
+
+}  // namespace lshmoe

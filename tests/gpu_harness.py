@@ -1,0 +1,129 @@
+"""Shared plumbing of the GPU parity tests: move storage arrays to the device,
+run the three C-ABI calls through the binding, compare with the oracle.
+
+Stage isolation: a token whose two largest rotated coordinates are within
+1e-4 relative of each other may legally hash to the runner-up vertex in
+binary32.  Such positions are counted; every later stage is then compared
+with the oracle evaluated on the bucket ids the GPU produced, so that one
+legal flip does not shift every offset after it.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2411_08446_amd as lsh
+
+TIE_MARGIN = 1e-4
+TOL = {"f32": 1e-5, "bf16": 2e-2}     # row-scaled: max_j |gpu - ref| <= tol * max_j |ref|
+
+
+def to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).cuda()
+    return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_storage(t: torch.Tensor, dtype: str) -> np.ndarray:
+    if dtype == "f32":
+        return t.detach().cpu().numpy()
+    return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@dataclass
+class GpuRun:
+    bucket: np.ndarray
+    out: "lsh.CompressOutputs"
+    S: int
+    centroids: np.ndarray     # storage, [S, d]
+    expert_out: np.ndarray    # storage, [S, d]
+    y: np.ndarray             # storage, [N, d]
+    ties: int
+
+
+def check_hash(bucket_gpu: np.ndarray, tokens, rot, dtype):
+    """Bit-exact against the oracle except at near ties, where the runner-up
+    vertex is also accepted.  Returns the number of accepted flips and the
+    number of near-tie positions."""
+    L, r, _ = rot.shape
+    b_ref, code, margin, runner = oracle.hash_ref(tokens, rot, dtype)
+    digits = np.empty_like(code)
+    rem = bucket_gpu.astype(np.uint64).copy()
+    for l in range(L - 1, -1, -1):
+        digits[:, l] = (rem % np.uint64(2 * r)).astype(np.int32)
+        rem //= np.uint64(2 * r)
+    assert np.all(rem == 0), "bucket id out of range"
+    diff = digits != code
+    bad = diff & ~((margin < TIE_MARGIN) & (digits == runner))
+    assert not bad.any(), "hash mismatch away from a near tie at (token, hash) %s" % (np.argwhere(bad)[:8].tolist(),)
+    return int(diff.sum()), int((margin < TIE_MARGIN).sum())
+
+
+def assert_rows_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str, tol=None):
+    tol = TOL[dtype] if tol is None else tol
+    err = oracle.row_rel_err(oracle.widen(got, dtype), oracle.widen(ref, dtype))
+    worst = int(np.argmax(err)) if err.size else -1
+    assert err.size == 0 or err[worst] <= tol, "%s: row %d off by %.3g (tol %.3g)" % (what, worst, err[worst], tol)
+    return float(err.max()) if err.size else 0.0
+
+
+def run_and_check(tokens: np.ndarray, rot: np.ndarray, expert: np.ndarray, E: int, dtype: str, expert_fn,
+                  flags: int = 0, use_seg_offsets: bool = True, bucket_override: np.ndarray | None = None,
+                  centroid_tol=None) -> GpuRun:
+    """Run hash -> compress -> expert_fn -> decompress on the GPU and compare
+    every output with the oracle.  expert_fn maps a torch [S, d] tensor of
+    centroids to the expert output (same dtype)."""
+    T, d = tokens.shape
+    L, r, _ = rot.shape
+    k = expert.shape[1]
+    N = T * k
+    xt, rt = to_device(tokens, dtype), to_device(rot, dtype)
+    et = torch.from_numpy(np.ascontiguousarray(expert, dtype=np.int32)).cuda()
+    bt = torch.empty(T, dtype=torch.int64, device="cuda")
+    lsh.lshmoe_hash(xt, rt, bt)
+    torch.cuda.synchronize()
+    bucket = bt.cpu().numpy().view(np.uint64)
+    flips, near = check_hash(bucket, tokens, rot, dtype)
+    if bucket_override is not None:
+        bucket = np.ascontiguousarray(bucket_override, dtype=np.uint64)
+        bt = torch.from_numpy(bucket.view(np.int64)).cuda()
+
+    out = lsh.CompressOutputs.allocate(T, d, k, E, L, r, xt.dtype)
+    # poison the outputs so stale values cannot pass
+    for t in (out.seg_offsets, out.seg_expert, out.expert_offsets, out.perm, out.seg_of, out.num_segments):
+        t.fill_(-7)
+    lsh.lshmoe_compress(xt, et, bt, E, L, r, out)
+    torch.cuda.synchronize()
+    g = oracle.group_ref(expert, bucket, E)
+    S = int(out.num_segments.item())
+    assert S == g["S"]
+    assert np.array_equal(out.seg_offsets[:S + 1].cpu().numpy(), g["seg_offsets"])
+    assert np.array_equal(out.seg_expert[:S].cpu().numpy(), g["seg_expert"])
+    assert np.array_equal(out.expert_offsets.cpu().numpy(), g["expert_offsets"])
+    assert np.array_equal(out.seg_of.cpu().numpy(), g["seg_of"])
+    assert np.array_equal(out.perm.cpu().numpy(), g["perm"])          # stable: bit-exact, not only as sets
+
+    c_gpu = to_storage(out.centroids[:S], dtype)
+    c_ref = oracle.centroid_ref(tokens, g["perm"], g["seg_offsets"], k, dtype)
+    assert_rows_close(c_gpu, c_ref, dtype, "centroid", centroid_tol)
+    single = np.diff(g["seg_offsets"]) == 1
+    first_tok = g["perm"][g["seg_offsets"][:-1]] // k
+    assert np.array_equal(c_gpu[single], tokens[first_tok[single]]), "one-member centroid must equal its token"
+
+    ec_t = expert_fn(out.centroids[:S]).contiguous()
+    ec = to_storage(ec_t, dtype)
+    yt = torch.full((T, k, d), float("nan"), dtype=xt.dtype, device="cuda")
+    lsh.lshmoe_decompress(xt, out.centroids, ec_t, out.seg_of, out.seg_offsets if use_seg_offsets else None,
+                          k, yt, flags=flags)
+    torch.cuda.synchronize()
+    y_gpu = to_storage(yt.view(N, d), dtype)
+    y_ref = oracle.restore_ref(tokens, c_gpu, ec, g["seg_of"], k, dtype, no_residual=bool(flags & 1))
+    assert_rows_close(y_gpu, y_ref, dtype, "restore")
+    if not (flags & 1):
+        rows = single[g["seg_of"]]
+        assert np.array_equal(oracle.widen(y_gpu[rows], dtype), oracle.widen(ec[g["seg_of"]][rows], dtype) + 0.0), \
+            "one-member clusters must return the expert output exactly"
+    return GpuRun(bucket, out, S, c_gpu, ec, y_gpu, flips)

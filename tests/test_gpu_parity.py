@@ -1,0 +1,166 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on the same seeded inputs.  Integer outputs bit-exact (hash ids
+modulo near ties, which are counted); centroids and restored rows within
+1e-5 (fp32) / 2e-2 (bf16) row-scaled."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import gpu_harness
+    gpu_harness.lsh.load_library()
+    return gpu_harness
+
+
+def _standin(cfg, seed):
+    return lambda c: synth.expert_standin(c, cfg, seed)
+
+
+def _rand_inputs(seed, T, d, k, E, L, r, dtype, centers=None, sigma=0.1):
+    rng = np.random.default_rng(seed)
+    if centers:
+        ctr = rng.standard_normal((centers, d)).astype(np.float32)
+        x = ctr[rng.integers(0, centers, T)] + sigma * rng.standard_normal((T, d)).astype(np.float32)
+    else:
+        x = rng.standard_normal((T, d)).astype(np.float32)
+    tokens = synth.f32_to_storage(x, dtype)
+    rot = synth.f32_to_storage(rng.standard_normal((L, r, d)).astype(np.float32), dtype)
+    expert = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    return tokens, rot, expert
+
+
+def _scale_fn(c):
+    return (c * 0.5 + 1.0).to(c.dtype)
+
+
+# ------------------------------------------------------------------ named configs
+@pytest.mark.parametrize("name,T", [("tiny", None), ("swin", 3001), ("roberta", 2500), ("gpt", 2077), ("t5", 1500)])
+def test_named_configs_reduced(H, name, T):
+    cfg = synth.config(name) if T is None else synth.config(name, T=T, centers=max(8, synth.config(name).centers * T // synth.config(name).T))
+    w = synth.generate(cfg)
+    print("case", cfg.name, "T", cfg.T, flush=True)
+    run = H.run_and_check(w.tokens, w.rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
+    print("  S/N %.3f  tie flips %d" % (run.S / cfg.N, run.ties), flush=True)
+
+
+@pytest.mark.parametrize("name", ["swin", "roberta", "gpt", "t5"])
+def test_named_configs_full_size(H, name):
+    cfg = synth.config(name)
+    w = synth.generate(cfg)
+    print("case", cfg.name, "full size T", cfg.T, flush=True)
+    run = H.run_and_check(w.tokens, w.rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
+    print("  S/N %.3f  tie flips %d" % (run.S / cfg.N, run.ties), flush=True)
+
+
+def test_content_correlated_gate_long_segments(H):
+    # the regime the paper measured: same-cluster tokens go to the same expert -> long clusters
+    cfg = synth.config("swin", T=6000, centers=40, gate="center_mod")
+    w = synth.generate(cfg)
+    run = H.run_and_check(w.tokens, w.rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
+    assert run.S / cfg.N < 0.3
+
+
+# ------------------------------------------------------------------ shapes and edge cases
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,d,k,E,L,r", [
+    (1, 8, 1, 1, 1, 2),          # smallest everything
+    (37, 16, 2, 3, 1, 3),        # odd r, ragged T
+    (129, 24, 1, 5, 3, 5),       # one token past a block of 128
+    (1000, 40, 3, 7, 2, 12),     # r not a multiple of 8
+    (513, 64, 2, 300, 4, 16),    # many experts (9 expert bits)
+    (300, 32, 4, 4, 8, 64),      # k == E, 56 bucket bits
+    (700, 264, 1, 2, 2, 256),    # r at the supported maximum, two passes over the tokens
+    (2500, 128, 2, 8, 5, 40),    # 200 rows of R in one pass, odd tile split
+    (640, 72, 1, 6, 6, 8),       # the paper's default count of hash functions
+])
+def test_shapes(H, dtype, T, d, k, E, L, r):
+    tokens, rot, expert = _rand_inputs(100 + T, T, d, k, E, L, r, dtype, centers=max(2, T // 6))
+    H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_all_tokens_identical_one_cluster(H, dtype):
+    T, d, E = 3000, 64, 1
+    tokens, rot, _ = _rand_inputs(7, 1, d, 1, E, 2, 16, dtype)
+    tokens = np.repeat(tokens, T, axis=0)
+    expert = np.zeros((T, 1), np.int32)
+    run = H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn)
+    assert run.S == 1
+    assert np.array_equal(run.centroids[0], tokens[0])      # mean of identical rows is the row, exactly
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_every_token_its_own_cluster_reconstructs_exactly(H, dtype):
+    # supplied bucket ids are all distinct: every cluster has one member, Y == E(x) bit for bit
+    T, d, k, E, L, r = 1111, 48, 2, 4, 4, 64
+    tokens, rot, expert = _rand_inputs(8, T, d, k, E, L, r, dtype)
+    ids = np.random.default_rng(3).permutation(T).astype(np.uint64) * np.uint64(104729)
+    run = H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn, bucket_override=ids)
+    assert run.S == T * k
+    assert np.array_equal(run.y, run.expert_out[run.out.seg_of.cpu().numpy()])
+
+
+def test_zero_tokens_and_exact_ties(H):
+    # all-zero tokens hash to code 0 in every hash; +-tied coordinates resolve to the lowest index
+    d, r, L = 16, 8, 2
+    rot = np.zeros((L, r, d), np.float32)
+    rot[0, np.arange(r), np.arange(r)] = 1.0
+    rot[1, np.arange(r), np.arange(r) + 8] = 1.0
+    x = np.zeros((6, d), np.float32)
+    x[1, 2] = 3.0; x[1, 5] = -3.0            # tie between coordinates 2 (+) and 5 (-) -> 2
+    x[2, 7] = -1.0; x[2, 0] = -1.0           # tie 0, 7 both negative -> 0 + r
+    x[3, 8 + 4] = 2.0; x[3, 8 + 6] = 2.0     # second hash tie -> 4
+    x[4, 3] = -0.0                           # negative zero counts as positive
+    x[5, :] = 1.0                            # all equal
+    expert = np.zeros((6, 1), np.int32)
+    run = H.run_and_check(x, rot, expert, 1, "f32", _scale_fn)
+    assert run.bucket.tolist() == [0, 2 * 16, 8 * 16, 4, 0, 0]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_no_residual_flag_and_without_seg_offsets(H, dtype):
+    tokens, rot, expert = _rand_inputs(9, 900, 32, 2, 6, 2, 8, dtype, centers=30)
+    H.run_and_check(tokens, rot, expert, 6, dtype, _scale_fn, flags=H.lsh.LSHMOE_FLAG_NO_RESIDUAL)
+    H.run_and_check(tokens, rot, expert, 6, dtype, _scale_fn, use_seg_offsets=False)
+
+
+def test_deterministic_across_runs(H):
+    cfg = synth.config("gpt", T=4000, centers=300)
+    w = synth.generate(cfg)
+    a = H.run_and_check(w.tokens, w.rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
+    b = H.run_and_check(w.tokens, w.rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
+    assert np.array_equal(a.bucket, b.bucket) and np.array_equal(a.centroids, b.centroids) and np.array_equal(a.y, b.y)
+
+
+def test_outputs_do_not_overrun(H):
+    # canaries after every compress output stay untouched
+    T, d, k, E, L, r = 777, 32, 2, 5, 2, 16
+    tokens, rot, expert = _rand_inputs(10, T, d, k, E, L, r, "bf16", centers=50)
+    lsh = H.lsh
+    N = T * k
+    xt, rt = H.to_device(tokens, "bf16"), H.to_device(rot, "bf16")
+    et = torch.from_numpy(expert).cuda()
+    bt = torch.empty(T + 8, dtype=torch.int64, device="cuda").fill_(-1)
+    lsh.lshmoe_hash(xt, rt, bt[:T])
+    out = lsh.CompressOutputs.allocate(T, d, k, E, L, r, xt.dtype)
+    pad = 16
+    big = {n: torch.full((getattr(out, n).numel() + pad,), -3, dtype=torch.int32, device="cuda")
+           for n in ("seg_offsets", "seg_expert", "expert_offsets", "perm", "seg_of", "num_segments")}
+    cent = torch.full((N + 2, d), 7.0, dtype=xt.dtype, device="cuda")
+    sub = lsh.CompressOutputs(cent[:N], *(big[n][:getattr(out, n).numel()] for n in
+                                           ("seg_offsets", "seg_expert", "expert_offsets", "perm", "seg_of",
+                                            "num_segments")), out.workspace)
+    lsh.lshmoe_compress(xt, et, bt[:T], E, L, r, sub)
+    torch.cuda.synchronize()
+    assert torch.all(bt[T:] == -1)
+    for n, t in big.items():
+        assert torch.all(t[-pad:] == -3), n
+    assert torch.all(cent[N:] == 7.0)
+    S = int(sub.num_segments.item())
+    assert torch.all(cent[S:N] == 7.0)       # rows past S are left alone
