@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the LSH-MoE compression path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload t5]
+
+One step = one pass of the whole path over one batch of synthetic tokens that
+are already resident in HBM: lshmoe_hash -> lshmoe_compress (group + centroid)
+-> lshmoe_decompress.  The expert stand-in that sits between compress and
+decompress is evaluated once, before timing, on the centroids of the same
+inputs; its output buffer is what every timed decompress reads.
+
+Prints ONE JSON line: tokens/s for the step, the roofline figures of the
+dominant kernel (the restore kernel) measured with events on the launch
+stream inside the timed loop, per-stage times, and the CPU oracle timed on a
+bounded sample of the same workload as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def _fail(msg: str, code: int = 2):
+    sys.stderr.write(msg + "\n")
+    sys.exit(code)
+
+
+def cpu_baseline(w, sample_tokens: int):
+    """Time the CPU oracle, as it stands, on the first `sample_tokens` tokens."""
+    import numpy as np
+    import oracle
+    from workloads import synth
+    cfg = w.cfg
+    Ts = min(sample_tokens, cfg.T)
+    tokens, expert = w.tokens[:Ts], w.expert[:Ts]
+    t0 = time.perf_counter()
+    bucket, _, _, _ = oracle.hash_ref(tokens, w.rot, cfg.dtype)
+    t1 = time.perf_counter()
+    g = oracle.group_ref(expert, bucket, cfg.E)
+    t2 = time.perf_counter()
+    c = oracle.centroid_ref(tokens, g["perm"], g["seg_offsets"], cfg.k, cfg.dtype)
+    t3 = time.perf_counter()
+    # expert output stand-in for the sample: any [S, d] array serves for timing the restore
+    y = oracle.restore_ref(tokens, c, c, g["seg_of"], cfg.k, cfg.dtype)
+    t4 = time.perf_counter()
+    del y
+    try:
+        import threadpoolctl
+        threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    total = t4 - t0
+    return {
+        "value": Ts / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": "first %d of %d tokens of the same workload; numpy float64 oracle, matmul step on %d BLAS "
+                  "threads, other steps on 1" % (Ts, cfg.T, threads),
+        "seconds": {"hash": t1 - t0, "group": t2 - t1, "centroid": t3 - t2, "restore": t4 - t3},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="t5", choices=["tiny", "swin", "roberta", "gpt", "t5"])
+    ap.add_argument("--gate", default=None, help="override the gate kind (e.g. 'content' for the supplementary run)")
+    ap.add_argument("--copies", type=int, default=2, help="independent input copies rotated between steps")
+    ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens in the CPU-oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        _fail("bench.py: this path is single-GPU by construction (no collectives are built); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        _fail("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    import paper_2411_08446_amd as lsh
+    from workloads import synth
+
+    lsh.load_library()
+    cfg = synth.config(args.workload, **({"gate": args.gate} if args.gate else {}))
+    w = synth.generate(cfg)
+    T, d, k, E, L, r, N = cfg.T, cfg.d, cfg.k, cfg.E, cfg.L, cfg.r, cfg.N
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    item = cfg.itemsize
+
+    def dev(arr):
+        if cfg.dtype == "f32":
+            return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+        return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).cuda().view(torch.bfloat16)
+
+    copies = max(1, args.copies)
+    xs = [dev(w.tokens) for _ in range(copies)]
+    rot = dev(w.rot)
+    expert = torch.from_numpy(w.expert).cuda()
+    bucket = torch.empty(T, dtype=torch.int64, device="cuda")
+    outs = [lsh.CompressOutputs.allocate(T, d, k, E, L, r, tdt) for _ in range(copies)]
+    ys = [torch.empty((T, k, d), dtype=tdt, device="cuda") for _ in range(copies)]
+
+    # untimed: centroids of these inputs -> expert stand-in output
+    lsh.lshmoe_hash(xs[0], rot, bucket)
+    lsh.lshmoe_compress(xs[0], expert, bucket, E, L, r, outs[0])
+    torch.cuda.synchronize()
+    S = int(outs[0].num_segments.item())
+    ecs = []
+    for i in range(copies):
+        ec = torch.empty((N, d), dtype=tdt, device="cuda")
+        ec[:S] = synth.expert_standin(outs[0].centroids[:S], cfg, w.seed)
+        ecs.append(ec)
+    seg_len = np.diff(outs[0].seg_offsets[:S + 1].cpu().numpy())
+    n_single = int((seg_len == 1).sum())
+
+    def step(i, ev=None):
+        c = i % copies
+        x, o = xs[c], outs[c]
+        if ev: ev[0].record()
+        lsh.lshmoe_hash(x, rot, bucket)
+        if ev: ev[1].record()
+        lsh.lshmoe_compress(x, expert, bucket, E, L, r, o)
+        if ev: ev[2].record()
+        lsh.lshmoe_decompress(x, o.centroids, ecs[c], o.seg_of, o.seg_offsets, k, ys[c])
+        if ev: ev[3].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    stage_ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in events])
+    hash_ms, comp_ms, dec_ms = stage_ms.mean(axis=0)
+
+    # algorithmic bytes of the restore kernel for this workload: expert-output row read and output row
+    # written for every assignment; token row and centroid row read only by members of multi-member clusters
+    row = d * item
+    n_multi_assign = N - n_single
+    n_multi_seg = S - n_single
+    restore_bytes = (S + N + n_multi_assign + n_multi_seg) * row + 4 * N + 4 * (S + 1)
+    restore_bytes_noskip = (T + 2 * S + N) * row + 4 * N
+    achieved = restore_bytes / (dec_ms * 1e-3) / 1e9
+    hash_flops = 2.0 * T * d * L * r
+    result = {
+        "metric": "tokens/sec hash+compress+decompress per GPU",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "%s: T=%d d=%d k=%d E=%d L=%d r=%d, Gaussian mixture of %d centers, gate=%s" %
+                               (cfg.name, T, d, k, E, L, r, cfg.centers, cfg.gate),
+                   "tokens": T, "assignments": N, "segments": S, "compression_rate": S / N,
+                   "single_member_segments": n_single, "input_copies_rotated": copies},
+        "roofline": {"kernel": "restore_kernel (lshmoe_decompress)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes": restore_bytes,
+                     "algorithmic_bytes_without_singleton_skip": restore_bytes_noskip,
+                     "avg_launch_ms": float(dec_ms)},
+        "stages_ms": {"hash": float(hash_ms), "compress": float(comp_ms), "decompress": float(dec_ms)},
+        "stages_p50_ms": {n: float(np.median(stage_ms[:, j])) for j, n in enumerate(("hash", "compress", "decompress"))},
+        "hash_mfma": {"tflops": hash_flops / (hash_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS[cfg.dtype],
+                      "frac": hash_flops / (hash_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype],
+                      "token_read_gbs": T * row / (hash_ms * 1e-3) / 1e9},
+    }
+    if args.cpu_sample > 0:
+        result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
