@@ -8,10 +8,27 @@
 // over a lane's own registers plus one exchange with lane l^32; the rotated
 // vectors are never written to memory.
 //
-// Both MFMA operands take 8 (bf16) or 1 (fp32) consecutive k values per lane
-// with the same (lane, element) -> k mapping, so which k a lane fetches is
-// free as long as A and B agree: every lane fetches one 16-byte piece of its
-// row per step.
+// Tiling.  A workgroup of 4 waves owns 4*NTK*32 tokens and all rows of one
+// "hash group" (as many whole hashes as fit in 256 rows of R).  Each wave
+// keeps MT x NTK accumulator tiles (all rows, its own NTK*32 tokens), so a
+// token's bucket id is completed inside one wave.  k is walked in chunks of
+// 128 bytes per row (4 MFMA steps).
+//
+//   tokens (B operand): the MFMA B layout wants, per lane, 16 bytes of one
+//     token's row.  Lanes fetch exactly that from global memory, straight
+//     into registers, XDEPTH-1 chunks ahead of use; measured on MI355X this
+//     access streams as fast as a fully coalesced read, so the tokens - the
+//     only HBM traffic of the kernel - never touch LDS.
+//   R (A operand): shared by the 4 waves, so each 128-byte chunk of the
+//     group's rows is staged in LDS (double buffered; the next chunk's global
+//     loads are in flight during the MFMAs of the current one).  The rows sit
+//     in LDS with an XOR swizzle of the 16-byte piece index by the row so
+//     that the fragment reads of 8 consecutive rows hit 8 different bank
+//     groups (measured: full 128 B/clk) while global loads stay coalesced.
+//
+// Both MFMA operands take their k values with the same (lane, element) -> k
+// mapping, so which k a lane supplies is free as long as A and B agree: the
+// lane half h = l/32 takes piece 2s + h of the chunk in step s.
 #include "kernels.h"
 
 namespace lshmoe {
@@ -21,128 +38,244 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-template <typename DT> struct Frag;
+template <typename DT> struct Mma;
 
-template <> struct Frag<BF16> {
-  static constexpr int kStepElems = 16;  // k values consumed per step by the two lane halves together
-  static constexpr int kLaneElems = 8;
-  uint4 q;
-  __device__ __forceinline__ void load(const char* row, int elem, int d) {
-    q = elem < d ? *reinterpret_cast<const uint4*>(row + (size_t)elem * 2) : make_uint4(0, 0, 0, 0);
-  }
-  static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, floatx16& c) {
-    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a.q), __builtin_bit_cast(bf16x8, b.q), c,
-                                                0, 0, 0);
+template <> struct Mma<BF16> {
+  static __device__ __forceinline__ void run(const uint4& a, const uint4& b, floatx16& c) {
+    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
   }
 };
 
-template <> struct Frag<F32> {
-  static constexpr int kStepElems = 8;
-  static constexpr int kLaneElems = 4;
-  float4 q;
-  __device__ __forceinline__ void load(const char* row, int elem, int d) {
-    q = elem < d ? *reinterpret_cast<const float4*>(row + (size_t)elem * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-  static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, floatx16& c) {
-    c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.q.x, b.q.x, c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.q.y, b.q.y, c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.q.z, b.q.z, c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.q.w, b.q.w, c, 0, 0, 0);
+template <> struct Mma<F32> {
+  static __device__ __forceinline__ void run(const uint4& a, const uint4& b, floatx16& c) {
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
   }
 };
 
-// One wave hashes 32 tokens.  The L hashes are processed in groups of `hpg`
-// whole hashes (hpg * r <= 32 * NT rows of R per group).
-template <typename DT, int NT>
+constexpr int kPieces = 8;   // 16-byte pieces per row per chunk
+constexpr int kSteps = 4;    // MFMA steps per chunk (two pieces, one per lane half, per step)
+
+__device__ __forceinline__ int swizzle(int row, int piece) { return piece ^ (row & 7); }
+
+template <typename DT, int MT, int NTK, int XDEPTH, bool ALIGNED8, bool KTAIL>
 __global__ __launch_bounds__(256) void hash_kernel(const char* __restrict__ tokens, const char* __restrict__ rot,
-                                                   uint64_t* __restrict__ bucket, uint32_t T, int d, int L, int r,
-                                                   int hpg) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+                                                   uint64_t* __restrict__ bucket, uint32_t T, int row_pieces, int L,
+                                                   int r, int hpg) {
+  constexpr int RA = MT * 32;              // rows of R staged per chunk
+  constexpr int SLOTS = RA * kPieces;      // 16-byte slots per LDS buffer
+  extern __shared__ uint4 lds[];           // [2][SLOTS]
+
+  const int tid = threadIdx.x;
+  __builtin_assume(tid >= 0 && tid < 256);
+  const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
-  const uint32_t token0 = (blockIdx.x * 4u + wave) * 32u;
-  if (token0 >= T) return;
-  const uint32_t tok = min(token0 + n, T - 1);
-  const size_t row_bytes = (size_t)d * Chunk<DT>::kItem;
-  const char* xrow = tokens + (size_t)tok * row_bytes;
-  uint64_t b = 0;
+  const uint32_t row_bytes = (uint32_t)row_pieces * 16u;
+  const int nchunks = ((row_pieces + kPieces - 1) / kPieces + XDEPTH - 1) / XDEPTH * XDEPTH;
+
+  // token rows of this lane (rows past the last token re-read it; their ids are never stored)
+  const uint32_t tok_wave = (blockIdx.x * 4u + wave) * (uint32_t)(NTK * 32);
+  const char* xrow[NTK];
+#pragma unroll
+  for (int u = 0; u < NTK; ++u)
+    xrow[u] = tokens + (size_t)min(tok_wave + (uint32_t)(u * 32 + n), T - 1) * row_bytes + h * 16;
+
+  // R staging: this thread always moves piece lp of rows r0, r0 + 32, ...
+  const int lp = tid & 7, r0 = tid >> 3;
+  const int st_slot = r0 * kPieces + swizzle(r0, lp);  // row offsets that are multiples of 8 keep the swizzle
+  int fa_slot[kSteps];
+#pragma unroll
+  for (int s = 0; s < kSteps; ++s) fa_slot[s] = n * kPieces + swizzle(n, 2 * s + h);
+
+  uint64_t b[NTK];
+#pragma unroll
+  for (int t = 0; t < NTK; ++t) b[t] = 0;
 
   for (int l0 = 0; l0 < L; l0 += hpg) {
     const int nh = min(hpg, L - l0);
-    const int rows = nh * r;
-    const char* arow[NT];
+    const int rows = nh * r;               // valid rows of R in this group (<= RA); rows past them repeat the last
+    const char* rot_group = rot + (size_t)l0 * r * row_bytes;
+    uint32_t off_a[MT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) arow[t] = rot + (size_t)(l0 * r + min(t * 32 + n, rows - 1)) * row_bytes;
-    floatx16 acc[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) acc[t][j] = 0.0f;
+    for (int i = 0; i < MT; ++i) off_a[i] = (uint32_t)min(r0 + i * 32, rows - 1) * row_bytes + lp * 16;
 
-    for (int kk = 0; kk < d; kk += Frag<DT>::kStepElems) {
-      const int elem = kk + h * Frag<DT>::kLaneElems;
-      Frag<DT> fb;
-      fb.load(xrow, elem, d);
+    uint4 stage[MT];
+    auto load_r = [&](int chunk) {
+      const bool in_row = !KTAIL || chunk * kPieces + lp < row_pieces;   // the k tail is zero filled
+      const char* a_base = rot_group + (size_t)chunk * (kPieces * 16);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        Frag<DT> fa;
-        fa.load(arow[t], elem, d);
-        Frag<DT>::mma(fa, fb, acc[t]);
+      for (int i = 0; i < MT; ++i)
+        stage[i] = in_row ? *reinterpret_cast<const uint4*>(a_base + off_a[i]) : make_uint4(0, 0, 0, 0);
+    };
+    auto store_r = [&](int buf) {
+      uint4* dst = lds + buf * SLOTS + st_slot;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) dst[i * 256] = stage[i];
+    };
+    uint4 xr[XDEPTH][NTK][kSteps];
+    auto load_x = [&](int chunk, uint4 (&dst)[NTK][kSteps]) {
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        const bool in_row = !KTAIL || chunk * kPieces + 2 * s + h < row_pieces;
+#pragma unroll
+        for (int u = 0; u < NTK; ++u)
+          dst[u][s] = in_row ? *reinterpret_cast<const uint4*>(xrow[u] + (size_t)chunk * (kPieces * 16) + s * 32)
+                             : make_uint4(0, 0, 0, 0);
+      }
+    };
+
+    floatx16 acc[MT][NTK];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int u = 0; u < NTK; ++u)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[t][u][j] = 0.0f;
+
+    __syncthreads();                       // previous group's readers are done with both buffers
+    load_r(0);
+#pragma unroll
+    for (int j = 0; j < XDEPTH - 1; ++j)
+      if (j < nchunks) load_x(j, xr[j]);
+    store_r(0);
+    __syncthreads();
+
+    // nchunks is a multiple of XDEPTH (the host rounds it up; with KTAIL the surplus chunks read as zeros),
+    // so the unrolled body needs no early exit and the accumulators stay in place
+    for (int c0 = 0; c0 < nchunks; c0 += XDEPTH) {
+#pragma unroll
+      for (int j = 0; j < XDEPTH; ++j) {
+        const int c = c0 + j;
+        const bool more = c + 1 < nchunks;
+        if (more) load_r(c + 1);
+        if (c + XDEPTH - 1 < nchunks) load_x(c + XDEPTH - 1, xr[(j + XDEPTH - 1) % XDEPTH]);
+        const uint4* buf = lds + (c & 1) * SLOTS;
+        // A fragments go through a small ring: the LDS read of (step, tile) i + kAhead is issued before the
+        // MFMAs of (step, tile) i, and the scheduler is told to keep that order
+        constexpr int kAhead = 3, kRing = 4, kFrags = kSteps * MT;
+        uint4 fa[kRing];
+#pragma unroll
+        for (int i = 0; i < kAhead && i < kFrags; ++i) fa[i] = buf[fa_slot[i / MT] + (i % MT) * 32 * kPieces];
+#pragma unroll
+        for (int i = 0; i < kFrags; ++i) {
+          if (i + kAhead < kFrags)
+            fa[(i + kAhead) % kRing] = buf[fa_slot[(i + kAhead) / MT] + ((i + kAhead) % MT) * 32 * kPieces];
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int u = 0; u < NTK; ++u) Mma<DT>::run(fa[i % kRing], xr[j][u][i / MT], acc[i % MT][u]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more) store_r((c + 1) & 1);
+        __syncthreads();
       }
     }
 
-    for (int lh = 0; lh < nh; ++lh) {
-      const int lo = lh * r, hi = lo + r;
-      float best = -1.0f;
-      int bi = 0x7fffffff;
-      bool neg = false;
+    // signed arg-max per hash of the group, from the accumulators
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        if (t * 32 + 31 < lo || t * 32 >= hi) continue;
+    for (int u = 0; u < NTK; ++u) {
+      for (int lh = 0; lh < nh; ++lh) {
+        const int lo = lh * r;
+        float best = -1.0f, bv = 0.0f;   // largest magnitude so far and the signed value that attains it
+        int bi = 0x7fffffff;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int mr = t * 32 + 8 * (j >> 2) + 4 * h + (j & 3);  // ascending in j for a fixed lane
-          const float v = acc[t][j];
-          const float av = fabsf(v);
-          if (mr >= lo && mr < hi && av > best) {
-            best = av;
-            bi = mr - lo;
-            neg = v < 0.0f;
+        for (int t = 0; t < MT; ++t) {
+          if (t * 32 + 31 < lo || t * 32 >= lo + r) continue;  // wave-uniform
+          if (ALIGNED8) {
+            // r and every hash boundary are multiples of 8: the four rows 8*jb + 4*h + (0..3) a lane holds
+            // of an 8-row block are inside the hash or outside it together, for every lane alike
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+              const int base = t * 32 + 8 * jb - lo;
+              if (base < 0 || base >= r) continue;  // wave-uniform
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const float v = acc[t][u][4 * jb + i];
+                const float av = fabsf(v);
+                if (av > best) {
+                  best = av;
+                  bi = base + 4 * h + i;
+                  bv = v;
+                }
+              }
+            }
+          } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const int rel = t * 32 + 8 * (j >> 2) + 4 * h + (j & 3) - lo;  // ascending in j for a fixed lane
+              const float v = acc[t][u][j];
+              const float av = (unsigned)rel < (unsigned)r ? fabsf(v) : -2.0f;
+              if (av > best) {
+                best = av;
+                bi = rel;
+                bv = v;
+              }
+            }
           }
         }
+        const float obest = __shfl_xor(best, 32, 64);
+        const int obi = __shfl_xor(bi, 32, 64);
+        const float obv = __shfl_xor(bv, 32, 64);
+        if (obest > best || (obest == best && obi < bi)) {
+          bi = obi;
+          bv = obv;
+        }
+        b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)(bi + (bv < 0.0f ? r : 0));
       }
-      const float obest = __shfl_xor(best, 32, 64);
-      const int obi = __shfl_xor(bi, 32, 64);
-      const int oneg = __shfl_xor((int)neg, 32, 64);
-      if (obest > best || (obest == best && obi < bi)) {
-        bi = obi;
-        neg = oneg != 0;
-      }
-      b = b * (uint64_t)(2 * r) + (uint64_t)(bi + (neg ? r : 0));
     }
   }
-  if (h == 0 && token0 + n < T) bucket[token0 + n] = b;
+  if (h == 0) {
+#pragma unroll
+    for (int u = 0; u < NTK; ++u) {
+      const uint32_t tok = tok_wave + (uint32_t)(u * 32 + n);
+      if (tok < T) bucket[tok] = b[u];
+    }
+  }
+}
+
+template <typename DT, int MT, int NTK, int XDEPTH, bool ALIGNED8, bool KTAIL>
+hipError_t launch_one(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
+                      hipStream_t stream) {
+  constexpr int kBlockTokens = 4 * NTK * 32;
+  constexpr size_t lds_bytes = (size_t)2 * MT * 32 * kPieces * 16;
+  static_assert(lds_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+  auto kern = hash_kernel<DT, MT, NTK, XDEPTH, ALIGNED8, KTAIL>;
+  if (lds_bytes > 48 * 1024) {
+    static bool raised = false;            // benign race: the attribute is idempotent
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
+  const dim3 grid((uint32_t)((T + kBlockTokens - 1) / kBlockTokens)), block(256);
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg);
+  return hipGetLastError();
 }
 
 template <typename DT>
 hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, int L, int r, uint64_t* bucket,
                         hipStream_t stream) {
-  int hpg = 256 / r;
+  int hpg = 256 / r;                       // whole hashes per pass over the tokens
   if (hpg > L) hpg = L;
   if (hpg < 1) return hipErrorInvalidValue;
-  const int nt = (hpg * r + 31) / 32;
-  const dim3 grid((uint32_t)((T + 127) / 128)), block(256);
+  const int mt = (hpg * r + 31) / 32;
+  const int row_pieces = (int)((size_t)d * Chunk<DT>::kItem / 16);
   auto x = (const char*)tokens;
   auto R = (const char*)rot;
-#define LSHMOE_HASH_CASE(NT)                                                                                   \
-  hipLaunchKernelGGL((hash_kernel<DT, NT>), grid, block, 0, stream, x, R, bucket, (uint32_t)T, d, L, r, hpg)
-  if (nt <= 1) LSHMOE_HASH_CASE(1);
-  else if (nt == 2) LSHMOE_HASH_CASE(2);
-  else if (nt == 3) LSHMOE_HASH_CASE(3);
-  else if (nt == 4) LSHMOE_HASH_CASE(4);
-  else if (nt <= 6) LSHMOE_HASH_CASE(6);
-  else LSHMOE_HASH_CASE(8);
-#undef LSHMOE_HASH_CASE
-  return hipGetLastError();
+  // fast instance: r a multiple of 8 (uniform epilogue) and rows a whole number of 4 x 128-byte chunks (no k tail)
+  const bool fast = r % 8 == 0 && row_pieces % (kPieces * 4) == 0;
+#define LSHMOE_HASH(MT, NTK, XD)                                                                      \
+  (fast ? launch_one<DT, MT, NTK, XD, true, false>(x, R, bucket, T, row_pieces, L, r, hpg, stream)    \
+        : launch_one<DT, MT, NTK, XD, false, true>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
+  if (mt <= 1) return LSHMOE_HASH(1, 1, 4);
+  if (mt == 2) return LSHMOE_HASH(2, 1, 4);
+  if (mt == 3) return LSHMOE_HASH(3, 1, 4);
+  if (mt == 4) return LSHMOE_HASH(4, 1, 4);
+  if (mt <= 6) return LSHMOE_HASH(6, 2, 2);
+  return LSHMOE_HASH(8, 2, 2);
+#undef LSHMOE_HASH
 }
 
 }  // namespace
