@@ -22,28 +22,33 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   return u >> 16;
 }
 
-// One 16-byte chunk of a row, widened to binary32 lanes.
-template <typename DT> struct Chunk;
+// Rows are moved as raw 16-byte pieces (uint4) and only widened to binary32
+// where arithmetic happens, so that loads in flight cost 4 registers each.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
-template <> struct Chunk<F32> {
+__device__ __forceinline__ uint4 load16(const char* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void store16(char* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
+// Streaming store: the line is not kept in the caches (outputs that nobody in this kernel reads again).
+__device__ __forceinline__ void store16_stream(char* p, uint4 v) {
+  const u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+}
+
+template <typename DT> struct Piece;   // arithmetic on one 16-byte piece
+
+template <> struct Piece<F32> {
   static constexpr int kElems = 4;
-  static constexpr int kItem = 4;
-  float v[4];
-  __device__ __forceinline__ void load(const void* row, int chunk) {
-    const float4 q = reinterpret_cast<const float4*>(row)[chunk];
-    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+  static __device__ __forceinline__ void widen(uint4 q, float (&v)[4]) {
+    v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y); v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w);
   }
-  __device__ __forceinline__ void store(void* row, int chunk) const {
-    reinterpret_cast<float4*>(row)[chunk] = make_float4(v[0], v[1], v[2], v[3]);
+  static __device__ __forceinline__ uint4 narrow(const float (&v)[4]) {
+    return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
   }
 };
 
-template <> struct Chunk<BF16> {
+template <> struct Piece<BF16> {
   static constexpr int kElems = 8;
-  static constexpr int kItem = 2;
-  float v[8];
-  __device__ __forceinline__ void load(const void* row, int chunk) {
-    const uint4 q = reinterpret_cast<const uint4*>(row)[chunk];
+  static __device__ __forceinline__ void widen(uint4 q, float (&v)[8]) {
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -51,12 +56,16 @@ template <> struct Chunk<BF16> {
       v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
     }
   }
-  __device__ __forceinline__ void store(void* row, int chunk) const {
+  static __device__ __forceinline__ uint4 narrow(const float (&v)[8]) {
     uint32_t w[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) w[i] = f32_to_bf16_bits(v[2 * i]) | (f32_to_bf16_bits(v[2 * i + 1]) << 16);
-    reinterpret_cast<uint4*>(row)[chunk] = make_uint4(w[0], w[1], w[2], w[3]);
+    return make_uint4(w[0], w[1], w[2], w[3]);
   }
 };
+
+template <typename DT> struct ItemSize;
+template <> struct ItemSize<F32> { static constexpr int value = 4; };
+template <> struct ItemSize<BF16> { static constexpr int value = 2; };
 
 }  // namespace lshmoe

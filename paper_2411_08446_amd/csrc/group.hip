@@ -68,29 +68,48 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(KeySource src, 
   hist[threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];  // bin-major: a scan over the table orders by (bin, tile)
 }
 
-// In-place exclusive scan of n 32-bit counters by one workgroup.
+// In-place exclusive scan of n 32-bit counters by one workgroup of 1024
+// threads: the array is walked in slabs of 4096 counters (one coalesced
+// 16-byte load per thread), carrying the running total from slab to slab.
 __global__ __launch_bounds__(1024) void scan_kernel(uint32_t* __restrict__ data, uint32_t n) {
   __shared__ uint32_t wave_sum[16];
-  const uint32_t per = (n + 1023u) / 1024u;
-  const uint32_t lo = min(threadIdx.x * per, n), hi = min(lo + per, n);
-  uint32_t sum = 0;
-  for (uint32_t i = lo; i < hi; ++i) sum += data[i];
-  // inclusive scan of the 1024 partial sums
+  __shared__ uint32_t carry_s;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t inc = sum;
+  uint32_t carry = 0;
+  for (uint32_t base = 0; base < n; base += 4096) {
+    const uint32_t i = base + threadIdx.x * 4;
+    uint32_t v[4] = {0, 0, 0, 0};
+    if (i + 4 <= n) {
+      const uint4 q = *reinterpret_cast<const uint4*>(data + i);
+      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else {
+      for (int j = 0; j < 4; ++j)
+        if (i + j < n) v[j] = data[i + j];
+    }
+    const uint32_t sum = v[0] + v[1] + v[2] + v[3];
+    uint32_t inc = sum;
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t v = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += v;
-  }
-  if (lane == 63) wave_sum[wave] = inc;
-  __syncthreads();
-  uint32_t run = inc - sum;
-  for (int w = 0; w < wave; ++w) run += wave_sum[w];
-  for (uint32_t i = lo; i < hi; ++i) {
-    const uint32_t v = data[i];
-    data[i] = run;
-    run += v;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t t = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) wave_sum[wave] = inc;
+    __syncthreads();
+    uint32_t run = carry + inc - sum;
+#pragma unroll
+    for (int w = 0; w < 16; ++w)
+      if (w < wave) run += wave_sum[w];
+    if (threadIdx.x == 1023) carry_s = run + sum;
+    uint32_t o[4];
+    o[0] = run; o[1] = o[0] + v[0]; o[2] = o[1] + v[1]; o[3] = o[2] + v[2];
+    if (i + 4 <= n) {
+      *reinterpret_cast<uint4*>(data + i) = make_uint4(o[0], o[1], o[2], o[3]);
+    } else {
+      for (int j = 0; j < 4; ++j)
+        if (i + j < n) data[i + j] = o[j];
+    }
+    __syncthreads();
+    carry = carry_s;
   }
 }
 

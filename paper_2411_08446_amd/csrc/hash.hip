@@ -261,7 +261,7 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
   if (hpg > L) hpg = L;
   if (hpg < 1) return hipErrorInvalidValue;
   const int mt = (hpg * r + 31) / 32;
-  const int row_pieces = (int)((size_t)d * Chunk<DT>::kItem / 16);
+  const int row_pieces = (int)((size_t)d * ItemSize<DT>::value / 16);
   auto x = (const char*)tokens;
   auto R = (const char*)rot;
   // fast instance: r a multiple of 8 (uniform epilogue) and rows a whole number of 4 x 128-byte chunks (no k tail)

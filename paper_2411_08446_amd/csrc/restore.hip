@@ -1,84 +1,115 @@
-// Restore with residual compensation (Eq. 4 and Eq. 5): one 16-byte chunk of
-// one output row per thread and unroll step.  HBM-bound gather: per output
-// row it reads the token row, the centroid row and the expert-output row and
-// writes one row; one-member clusters read only the expert-output row.
+// Restore with residual compensation (Eq. 4 and Eq. 5):
+//     out[a] = expert_out[s] + (tokens[a / k] - centroids[s]),   s = seg_of[a].
+//
+// HBM-bound gather: per output row it reads the expert-output row and, for
+// members of clusters with more than one member, the token row and the
+// centroid row; it writes one row.  A group of LPR lanes owns kRows
+// consecutive output rows (the k assignments of a token are consecutive, so
+// they share the token row) and strides over the 16-byte pieces; with rows of
+// 1 KB and more that is a whole wave, and the cluster lookups are wave-uniform
+// scalars.  Output rows are written with streaming stores.
 #include "kernels.h"
 
 namespace lshmoe {
 
-template <typename DT, int UNROLL>
+namespace {
+
+constexpr int kRows = 2;  // output rows a lane group works on at once
+
+template <int LPR> __device__ __forceinline__ int32_t uniform(int32_t v) {
+  return LPR == 64 ? __builtin_amdgcn_readfirstlane(v) : v;
+}
+
+template <typename DT, int LPR>
 __global__ __launch_bounds__(256) void restore_kernel(
     const char* __restrict__ tokens, const char* __restrict__ centroids, const char* __restrict__ expert_out,
     const int32_t* __restrict__ seg_of, const int32_t* __restrict__ seg_offsets, char* __restrict__ out,
-    uint32_t N, uint32_t k, uint32_t cpr, uint32_t rows_per_sweep, uint32_t flags) {
-  const uint32_t g = blockIdx.x * 256u + threadIdx.x;
-  const uint32_t a0 = g / cpr;
-  const uint32_t c = g - a0 * cpr;
-  if (a0 >= rows_per_sweep) return;
+    uint32_t N, uint32_t k, uint32_t cpr, uint32_t flags) {
+  constexpr int G = 64 / LPR;
+  constexpr int E = Piece<DT>::kElems;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t a0 = (((blockIdx.x * 256u + threadIdx.x) >> 6) * G + lane / LPR) * kRows;
+  if (a0 >= N) return;
   const size_t row_bytes = (size_t)cpr * 16;
   const bool no_res = (flags & 1u) != 0;
 
-  int32_t s[UNROLL];
-  bool live[UNROLL], full[UNROLL];
+  int32_t s[kRows];
+  bool live[kRows], full[kRows];
 #pragma unroll
-  for (int u = 0; u < UNROLL; ++u) {
-    const uint32_t a = a0 + u * rows_per_sweep;
-    live[u] = a < N;
-    s[u] = live[u] ? seg_of[a] : 0;
+  for (int u = 0; u < kRows; ++u) {
+    live[u] = a0 + u < N;
+    s[u] = live[u] ? uniform<LPR>(seg_of[a0 + u]) : 0;
   }
 #pragma unroll
-  for (int u = 0; u < UNROLL; ++u) {
+  for (int u = 0; u < kRows; ++u) {
     full[u] = live[u] && !no_res;
-    if (full[u] && seg_offsets != nullptr) full[u] = (seg_offsets[s[u] + 1] - seg_offsets[s[u]]) != 1;
+    // a one-member cluster's centroid is its token bit for bit: the residual is exactly zero
+    if (full[u] && seg_offsets != nullptr)
+      full[u] = uniform<LPR>(seg_offsets[s[u] + 1]) - uniform<LPR>(seg_offsets[s[u]]) != 1;
   }
-  Chunk<DT> ec[UNROLL], x[UNROLL], cc[UNROLL];
+  for (uint32_t c = lane % LPR; c < cpr; c += LPR) {
+    uint4 ec[kRows], x[kRows], cc[kRows];
 #pragma unroll
-  for (int u = 0; u < UNROLL; ++u) {
-    if (live[u]) ec[u].load(expert_out + (size_t)s[u] * row_bytes, c);
-    if (full[u]) {
-      const uint32_t a = a0 + u * rows_per_sweep;
-      x[u].load(tokens + (size_t)(a / k) * row_bytes, c);
-      cc[u].load(centroids + (size_t)s[u] * row_bytes, c);
+    for (int u = 0; u < kRows; ++u) {
+      if (live[u]) ec[u] = load16(expert_out + (size_t)s[u] * row_bytes + c * 16);
+      if (full[u]) {
+        x[u] = load16(tokens + (size_t)((a0 + u) / k) * row_bytes + c * 16);
+        cc[u] = load16(centroids + (size_t)s[u] * row_bytes + c * 16);
+      }
     }
-  }
 #pragma unroll
-  for (int u = 0; u < UNROLL; ++u) {
-    if (!live[u]) continue;
-    const uint32_t a = a0 + u * rows_per_sweep;
-    Chunk<DT> y;
-    if (full[u]) {
+    for (int u = 0; u < kRows; ++u) {
+      if (!live[u]) continue;
+      uint4 y = ec[u];
+      if (!no_res) {
+        float e[E], xv[E], cv[E];
+        Piece<DT>::widen(ec[u], e);
+        if (full[u]) {
+          Piece<DT>::widen(x[u], xv);
+          Piece<DT>::widen(cc[u], cv);
 #pragma unroll
-      for (int i = 0; i < Chunk<DT>::kElems; ++i) y.v[i] = ec[u].v[i] + (x[u].v[i] - cc[u].v[i]);
-    } else if (no_res) {
+          for (int i = 0; i < E; ++i) e[i] += xv[i] - cv[i];
+        } else {
 #pragma unroll
-      for (int i = 0; i < Chunk<DT>::kElems; ++i) y.v[i] = ec[u].v[i];
-    } else {
-      // x == c bit for bit: the residual is +0, and e + (+0) maps -0 to +0
-#pragma unroll
-      for (int i = 0; i < Chunk<DT>::kElems; ++i) y.v[i] = ec[u].v[i] + 0.0f;
+          for (int i = 0; i < E; ++i) e[i] += 0.0f;  // e + (+0): only turns -0 into +0, as the full formula would
+        }
+        y = Piece<DT>::narrow(e);
+      }
+      store16_stream(out + (size_t)(a0 + u) * row_bytes + c * 16, y);
     }
-    y.store(out + (size_t)a * row_bytes, c);
   }
 }
 
+template <typename DT, int LPR>
+void launch_lpr(const void* tokens, const void* centroids, const void* expert_out, const int32_t* seg_of,
+                const int32_t* seg_offsets, void* out, int64_t N, int k, uint32_t cpr, uint32_t flags,
+                hipStream_t stream) {
+  constexpr int G = 64 / LPR;
+  const uint64_t groups = ((uint64_t)N + kRows - 1) / kRows;
+  const uint64_t waves = (groups + G - 1) / G;
+  const uint32_t blocks = (uint32_t)((waves + 3) / 4);
+  hipLaunchKernelGGL((restore_kernel<DT, LPR>), dim3(blocks), dim3(256), 0, stream, (const char*)tokens,
+                     (const char*)centroids, (const char*)expert_out, seg_of, seg_offsets, (char*)out, (uint32_t)N,
+                     (uint32_t)k, cpr, flags);
+}
+
+template <typename DT>
+void launch_typed(const void* tokens, const void* centroids, const void* expert_out, const int32_t* seg_of,
+                  const int32_t* seg_offsets, void* out, int64_t N, int k, uint32_t cpr, uint32_t flags,
+                  hipStream_t stream) {
+  if (cpr > 16) launch_lpr<DT, 64>(tokens, centroids, expert_out, seg_of, seg_offsets, out, N, k, cpr, flags, stream);
+  else if (cpr > 4) launch_lpr<DT, 16>(tokens, centroids, expert_out, seg_of, seg_offsets, out, N, k, cpr, flags, stream);
+  else launch_lpr<DT, 4>(tokens, centroids, expert_out, seg_of, seg_offsets, out, N, k, cpr, flags, stream);
+}
+
+}  // namespace
+
 hipError_t launch_restore(const void* tokens, const void* centroids, const void* expert_out,
-                          const int32_t* seg_of, const int32_t* seg_offsets, void* out,
-                          int64_t N, int k, int d, bool bf16, uint32_t flags, hipStream_t stream) {
-  constexpr int UNROLL = 4;
+                          const int32_t* seg_of, const int32_t* seg_offsets, void* out, int64_t N, int k, int d,
+                          bool bf16, uint32_t flags, hipStream_t stream) {
   const uint32_t cpr = (uint32_t)((size_t)d * (bf16 ? 2 : 4) / 16);
-  const uint32_t rows_per_sweep = (uint32_t)((N + UNROLL - 1) / UNROLL);
-  const uint64_t threads = (uint64_t)rows_per_sweep * cpr;
-  if (threads > 0xffffff00ull) return hipErrorInvalidValue;
-  const uint32_t blocks = (uint32_t)((threads + 255) / 256);
-  auto t = (const char*)tokens;
-  auto c = (const char*)centroids;
-  auto e = (const char*)expert_out;
-  if (bf16)
-    hipLaunchKernelGGL((restore_kernel<BF16, UNROLL>), dim3(blocks), dim3(256), 0, stream, t, c, e, seg_of,
-                       seg_offsets, (char*)out, (uint32_t)N, (uint32_t)k, cpr, rows_per_sweep, flags);
-  else
-    hipLaunchKernelGGL((restore_kernel<F32, UNROLL>), dim3(blocks), dim3(256), 0, stream, t, c, e, seg_of,
-                       seg_offsets, (char*)out, (uint32_t)N, (uint32_t)k, cpr, rows_per_sweep, flags);
+  if (bf16) launch_typed<BF16>(tokens, centroids, expert_out, seg_of, seg_offsets, out, N, k, cpr, flags, stream);
+  else launch_typed<F32>(tokens, centroids, expert_out, seg_of, seg_offsets, out, N, k, cpr, flags, stream);
   return hipGetLastError();
 }
 
