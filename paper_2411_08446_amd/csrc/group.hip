@@ -2,25 +2,35 @@
 // each expert's tokens into clusters by bucket id).
 //
 // A stable least-significant-digit radix sort of the packed key
-// (expert << bbits | bucket) carrying the assignment index, 8 bits per pass,
-// followed by a head-flag scan that numbers the clusters.  Integer work only;
-// every result is deterministic.  The arrays are a few MB at most, so the
-// step is bound by launch latency rather than by HBM.
+// (expert << bbits | bucket) carrying the assignment index, up to 9 bits per
+// pass, followed by a head-flag pass that numbers the clusters.  Integer work
+// only; every result is deterministic.  The arrays are a few MB at most, so
+// the step is bound by launch latency, not by HBM: the design goal is few
+// kernels.
 //
-// Per pass:  tile histogram -> exclusive scan of the (bin, tile) table ->
-// scatter.  Ranks inside a tile come from wave ballots: a wave of 64 keys
+// Ranks inside a tile of 2048 keys come from wave ballots: a wave of 64 keys
 // finds, for every lane, the lanes holding the same digit; tile order equals
 // element order, which keeps the sort stable.
+//
+// Small inputs (up to kFusedMaxTiles tiles; every paper-shaped layer): two
+// kernels per pass.  The histogram kernel writes the tile's digit counts as
+// one row of a tile-major table, and every scatter block derives its own
+// output offsets from that small table (sum of the rows before it, prefix
+// over the bins), so there is no scan launch.  (Accumulating the next pass's
+// table with global atomics from inside the scatter was measured slower than
+// the separate histogram launch: device-scope atomics cost ~8 us per pass.)
+// Large inputs: histogram, single-workgroup scan of the (bin, tile) table and
+// scatter per pass.
 #include "kernels.h"
 
 namespace lshmoe {
 
 namespace {
 
-constexpr int kBins = 256;
 constexpr int kSortThreads = 256;
 constexpr int kSortItems = kSortTile / kSortThreads;  // 8
 constexpr int kGroupsPerTile = kSortTile / kWave;     // 32 waves' worth of keys
+constexpr int kGhStride = kGroupsPerTile + 1;          // per-bin row of group counts, padded against bank conflicts
 constexpr int kSegThreads = 256;
 constexpr int kSegItems = kSegTile / kSegThreads;     // 4
 
@@ -47,25 +57,56 @@ __device__ __forceinline__ void load_item(const KeySource& src, uint32_t i, uint
   }
 }
 
-template <bool FIRST>
-__global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(KeySource src, uint32_t N, int shift,
-                                                                 uint32_t nblk, uint32_t* __restrict__ hist) {
-  __shared__ uint32_t h[kBins];
-  h[threadIdx.x] = 0;
-  __syncthreads();
-  const uint32_t base = blockIdx.x * kSortTile;
+// Exclusive scan of one value per thread across a 256-thread block.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_sum /*[4]*/, uint32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = v;
 #pragma unroll
-  for (int it = 0; it < kSortItems; ++it) {
-    const uint32_t i = base + it * kSortThreads + threadIdx.x;
-    if (i < N) {
-      uint64_t key;
-      int32_t idx;
-      load_item<FIRST>(src, i, key, idx);
-      atomicAdd(&h[(uint32_t)(key >> shift) & (kBins - 1)], 1u);
-    }
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wave_sum[wave] = inc;
+  __syncthreads();
+  uint32_t before = 0;
+  total = 0;
+#pragma unroll
+  for (int w = 0; w < 256 / kWave; ++w) {
+    if (w < wave) before += wave_sum[w];
+    total += wave_sum[w];
   }
   __syncthreads();
-  hist[threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];  // bin-major: a scan over the table orders by (bin, tile)
+  return before + inc - v;
+}
+
+// Tile histogram of one pass.  FUSED: row `tile` of a tile-major table.  Otherwise: column `tile` of a
+// bin-major table (scanned next).
+template <bool FIRST, bool FUSED>
+__global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(KeySource src, uint32_t N, int shift, uint32_t mask,
+                                                                 uint32_t nblk, uint32_t* __restrict__ table) {
+  __shared__ uint32_t h[kGroupBins];
+  h[threadIdx.x] = 0;
+  h[threadIdx.x + 256] = 0;
+  __syncthreads();
+  const uint32_t base = blockIdx.x * kSortTile;
+  uint64_t key[kSortItems];
+  int32_t idx[kSortItems];
+#pragma unroll
+  for (int it = 0; it < kSortItems; ++it)
+    load_item<FIRST>(src, min(base + it * kSortThreads + threadIdx.x, N - 1), key[it], idx[it]);
+#pragma unroll
+  for (int it = 0; it < kSortItems; ++it)
+    if (base + it * kSortThreads + threadIdx.x < N) atomicAdd(&h[(uint32_t)(key[it] >> shift) & mask], 1u);
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const uint32_t bin = threadIdx.x + 256 * j;
+    if (FUSED) {
+      table[blockIdx.x * kGroupBins + bin] = h[bin];
+    } else if (bin <= mask) {
+      table[bin * nblk + blockIdx.x] = h[bin];  // bin-major: a scan over the table orders by (bin, tile)
+    }
+  }
 }
 
 // In-place exclusive scan of n 32-bit counters by one workgroup of 1024
@@ -113,13 +154,21 @@ __global__ __launch_bounds__(1024) void scan_kernel(uint32_t* __restrict__ data,
   }
 }
 
-template <bool FIRST>
-__global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource src, uint32_t N, int shift,
-                                                                    uint32_t nblk, const uint32_t* __restrict__ hist,
+struct PassArgs {
+  int shift;            // this pass's digit is (key >> shift) & mask
+  uint32_t mask;
+  uint32_t nblk;
+  const uint32_t* table;  // FUSED: tile-major counts of this pass; else the scanned bin-major offsets
+};
+
+template <bool FIRST, bool FUSED>
+__global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource src, uint32_t N, PassArgs a,
                                                                     uint64_t* __restrict__ dst_key,
                                                                     int32_t* __restrict__ dst_idx) {
-  __shared__ uint32_t gh[kGroupsPerTile][kBins];  // per 64-key group digit counts, then start offsets
-  for (int i = threadIdx.x; i < kGroupsPerTile * kBins; i += kSortThreads) (&gh[0][0])[i] = 0;
+  extern __shared__ uint32_t gh[];  // [kGroupBins][kGhStride] per-bin counts of each 64-key group, then start offsets
+  __shared__ uint32_t wave_sum[4];
+  __shared__ uint32_t part[2][2][kGroupBins];  // FUSED: [before/total][tile parity][bin]
+  for (int i = threadIdx.x; i < kGroupBins * kGhStride; i += kSortThreads) gh[i] = 0;
   __syncthreads();
   const uint32_t base = blockIdx.x * kSortTile;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -127,33 +176,91 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource sr
   uint64_t key[kSortItems];
   int32_t idx[kSortItems];
   uint32_t rank[kSortItems];
+  // all of the tile's loads are issued before the first use (positions past N re-read the last key and are
+  // masked out below), so the tile costs one memory round trip
+#pragma unroll
+  for (int it = 0; it < kSortItems; ++it)
+    load_item<FIRST>(src, min(base + it * kSortThreads + threadIdx.x, N - 1), key[it], idx[it]);
 #pragma unroll
   for (int it = 0; it < kSortItems; ++it) {
     const uint32_t i = base + it * kSortThreads + threadIdx.x;
     const bool valid = i < N;
-    key[it] = 0;
-    idx[it] = 0;
-    if (valid) load_item<FIRST>(src, i, key[it], idx[it]);
-    const uint32_t digit = (uint32_t)(key[it] >> shift) & (kBins - 1);
+    const uint32_t digit = (uint32_t)(key[it] >> a.shift) & a.mask;
     uint64_t same = __ballot(valid);
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
+    for (int b = 0; b < kMaxDigitBits; ++b) {
       const bool bit = (digit >> b) & 1u;
       const uint64_t bal = __ballot(bit);
       same &= bit ? bal : ~bal;
     }
     rank[it] = (uint32_t)__popcll(same & lt_mask);
-    if (valid && rank[it] == 0) gh[it * (kSortThreads / kWave) + wave][digit] = (uint32_t)__popcll(same);
+    if (valid && rank[it] == 0) gh[digit * kGhStride + it * (kSortThreads / kWave) + wave] = (uint32_t)__popcll(same);
   }
-  __syncthreads();
-  {
-    const int bin = threadIdx.x;
-    uint32_t run = hist[bin * nblk + blockIdx.x];
-#pragma unroll 8
+
+  // first output position of each bin for this tile
+  uint32_t start[2];
+  if (FUSED) {
+    // counts[tile][bin]: keys of bin b in earlier tiles come first, after all keys of smaller bins
+    // Threads 0..127 walk the even tiles' rows, threads 128..255 the odd ones, four bins (16 bytes) each,
+    // in batches of independent loads; the two parities are then combined through LDS.
+    {
+      const uint32_t parity = threadIdx.x >> 7, b4 = (threadIdx.x & 127) * 4;
+      uint32_t bef[4] = {0, 0, 0, 0}, tot[4] = {0, 0, 0, 0};
+      for (uint32_t t0 = parity; t0 < a.nblk; t0 += 32) {
+        uint4 v[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const uint32_t t = t0 + 2 * q;
+          v[q] = t < a.nblk ? *reinterpret_cast<const uint4*>(a.table + t * kGroupBins + b4) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const bool earlier = t0 + 2 * q < blockIdx.x;
+          const uint32_t w[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            tot[j] += w[j];
+            bef[j] += earlier ? w[j] : 0u;
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        part[0][parity][b4 + j] = bef[j];
+        part[1][parity][b4 + j] = tot[j];
+      }
+    }
+    __syncthreads();
+    uint32_t before[2], total[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const uint32_t bin = threadIdx.x + 256 * j;
+      before[j] = part[0][0][bin] + part[0][1][bin];
+      total[j] = part[1][0][bin] + part[1][1][bin];
+    }
+    uint32_t half;  // keys in bins 0..255
+    start[0] = block_exclusive_scan(total[0], wave_sum, half) + before[0];
+    uint32_t unused;
+    start[1] = half + block_exclusive_scan(total[1], wave_sum, unused) + before[1];
+  } else {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const uint32_t bin = threadIdx.x + 256 * j;
+      start[j] = bin <= a.mask ? a.table[bin * a.nblk + blockIdx.x] : 0;
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {  // counts -> start offsets along the bin's row (independent reads, then register adds)
+    uint32_t* row = gh + (threadIdx.x + 256 * j) * kGhStride;
+    uint32_t c[kGroupsPerTile];
+#pragma unroll
+    for (int g = 0; g < kGroupsPerTile; ++g) c[g] = row[g];
+    uint32_t run = start[j];
+#pragma unroll
     for (int g = 0; g < kGroupsPerTile; ++g) {
-      const uint32_t c = gh[g][bin];
-      gh[g][bin] = run;
-      run += c;
+      row[g] = run;
+      run += c[g];
     }
   }
   __syncthreads();
@@ -161,89 +268,90 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource sr
   for (int it = 0; it < kSortItems; ++it) {
     const uint32_t i = base + it * kSortThreads + threadIdx.x;
     if (i < N) {
-      const uint32_t digit = (uint32_t)(key[it] >> shift) & (kBins - 1);
-      const uint32_t pos = gh[it * (kSortThreads / kWave) + wave][digit] + rank[it];
+      const uint32_t digit = (uint32_t)(key[it] >> a.shift) & a.mask;
+      const uint32_t pos = gh[digit * kGhStride + it * (kSortThreads / kWave) + wave] + rank[it];
       dst_key[pos] = key[it];
       dst_idx[pos] = idx[it];
     }
   }
 }
 
-// Exclusive scan of one value per thread across a 256-thread block.
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_sum /*[4]*/, uint32_t& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t inc = v;
+// Head flags of kSegItems consecutive sorted positions starting at `base`: position p starts a cluster when
+// its key differs from the key before it.  The keys are fetched up front (indices clamped into range).
+__device__ __forceinline__ void load_heads(const uint64_t* __restrict__ key, uint32_t base, uint32_t N,
+                                           uint64_t (&kv)[kSegItems + 1], bool (&head)[kSegItems]) {
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t t = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += t;
+  for (int it = 0; it <= kSegItems; ++it) {
+    const uint32_t p = base + it;  // kv[it] is the key at position p - 1
+    kv[it] = key[min(p == 0 ? 0u : p - 1, N - 1)];
   }
-  if (lane == 63) wave_sum[wave] = inc;
-  __syncthreads();
-  uint32_t before = 0;
-  total = 0;
 #pragma unroll
-  for (int w = 0; w < kSegThreads / kWave; ++w) {
-    if (w < wave) before += wave_sum[w];
-    total += wave_sum[w];
+  for (int it = 0; it < kSegItems; ++it) {
+    const uint32_t p = base + it;
+    head[it] = p < N && (p == 0 || kv[it + 1] != kv[it]);
   }
-  __syncthreads();
-  return before + inc - v;
-}
-
-__device__ __forceinline__ bool is_head(const uint64_t* __restrict__ key, uint32_t p) {
-  return p == 0 || key[p] != key[p - 1];
 }
 
 __global__ __launch_bounds__(kSegThreads) void seg_count_kernel(const uint64_t* __restrict__ key, uint32_t N,
                                                                 uint32_t nblk, uint32_t* __restrict__ blocksum) {
   __shared__ uint32_t wave_sum[kSegThreads / kWave];
   const uint32_t base = blockIdx.x * kSegTile + threadIdx.x * kSegItems;
+  uint64_t kv[kSegItems + 1];
+  bool head[kSegItems];
+  load_heads(key, base, N, kv, head);
   uint32_t c = 0;
 #pragma unroll
-  for (int it = 0; it < kSegItems; ++it) {
-    const uint32_t p = base + it;
-    if (p < N && is_head(key, p)) ++c;
-  }
+  for (int it = 0; it < kSegItems; ++it) c += head[it] ? 1u : 0u;
   uint32_t total;
   block_exclusive_scan(c, wave_sum, total);
   if (threadIdx.x == 0) {
     blocksum[blockIdx.x] = total;
-    if (blockIdx.x == 0) blocksum[nblk] = 0;  // after the scan this slot holds the grand total
+    if (blockIdx.x == 0) blocksum[nblk] = 0;  // after a scan this slot holds the grand total
   }
 }
 
+// SELF_PREFIX: blocksum holds per-tile head counts and the block adds up the tiles before it itself;
+// otherwise blocksum has been scanned.
+template <bool SELF_PREFIX>
 __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(
     const uint64_t* __restrict__ key, const int32_t* __restrict__ perm, uint32_t N, uint32_t E, int bbits,
     const uint32_t* __restrict__ blocksum, int32_t* __restrict__ seg_offsets, int32_t* __restrict__ seg_expert,
     int32_t* __restrict__ expert_offsets, int32_t* __restrict__ seg_of, int32_t* __restrict__ num_segments) {
   __shared__ uint32_t wave_sum[kSegThreads / kWave];
+  uint32_t tiles_before = 0;
+  if (SELF_PREFIX) {
+    uint32_t part = 0;
+    for (uint32_t t = threadIdx.x; t < blockIdx.x; t += kSegThreads) part += blocksum[t];
+    block_exclusive_scan(part, wave_sum, tiles_before);
+  } else {
+    tiles_before = blocksum[blockIdx.x];
+  }
   const uint32_t base = blockIdx.x * kSegTile + threadIdx.x * kSegItems;
+  uint64_t kv[kSegItems + 1];
   bool head[kSegItems];
+  load_heads(key, base, N, kv, head);
+  int32_t a[kSegItems];
+#pragma unroll
+  for (int it = 0; it < kSegItems; ++it) a[it] = perm[min(base + it, N - 1)];
   uint32_t c = 0;
 #pragma unroll
-  for (int it = 0; it < kSegItems; ++it) {
-    const uint32_t p = base + it;
-    head[it] = p < N && is_head(key, p);
-    c += head[it] ? 1u : 0u;
-  }
+  for (int it = 0; it < kSegItems; ++it) c += head[it] ? 1u : 0u;
   uint32_t total;
-  uint32_t seg = blocksum[blockIdx.x] + block_exclusive_scan(c, wave_sum, total);  // heads before this thread
+  uint32_t seg = tiles_before + block_exclusive_scan(c, wave_sum, total);  // heads before this thread
 #pragma unroll
   for (int it = 0; it < kSegItems; ++it) {
     const uint32_t p = base + it;
     if (p >= N) break;
+    const uint32_t e = (uint32_t)(kv[it + 1] >> bbits);
     if (head[it]) {
-      const uint32_t e = (uint32_t)(key[p] >> bbits);
       seg_offsets[seg] = (int32_t)p;
       seg_expert[seg] = (int32_t)e;
-      const uint32_t first = p == 0 ? 0u : (uint32_t)(key[p - 1] >> bbits) + 1u;
+      const uint32_t first = p == 0 ? 0u : (uint32_t)(kv[it] >> bbits) + 1u;
       for (uint32_t x = first; x <= e; ++x) expert_offsets[x] = (int32_t)seg;  // experts that start (or are empty) here
       ++seg;
     }
-    seg_of[perm[p]] = (int32_t)(seg - 1);
+    seg_of[a[it]] = (int32_t)(seg - 1);
     if (p == N - 1) {
-      const uint32_t e = (uint32_t)(key[p] >> bbits);
       for (uint32_t x = e + 1; x <= E; ++x) expert_offsets[x] = (int32_t)seg;
       seg_offsets[seg] = (int32_t)N;
       *num_segments = (int32_t)seg;
@@ -262,6 +370,22 @@ int bits_for(uint64_t max_value) {  // number of bits needed to hold max_value
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+constexpr size_t kScatterLds = (size_t)kGroupBins * kGhStride * 4;  // 66 KB
+
+template <bool FIRST, bool FUSED>
+hipError_t launch_scatter(const KeySource& src, uint32_t N, const PassArgs& a, uint64_t* dkey, int32_t* didx,
+                          hipStream_t stream) {
+  auto kern = sort_scatter_kernel<FIRST, FUSED>;
+  static bool raised = false;  // benign race: the attribute is idempotent
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLds);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(a.nblk), dim3(kSortThreads), kScatterLds, stream, src, N, a, dkey, didx);
+  return hipSuccess;
+}
+
 }  // namespace
 
 bool plan_group(int64_t T, int k, int E, int L, int r, GroupPlan* plan) {
@@ -271,11 +395,19 @@ bool plan_group(int64_t T, int k, int E, int L, int r, GroupPlan* plan) {
   p.N = T * k;
   p.ebits = bits_for((uint64_t)E - 1);
   p.bbits = bits_for(nb - 1);
-  if (p.ebits + p.bbits > 64) return false;
-  p.passes = (p.ebits + p.bbits + 7) / 8;
+  const int bits = p.ebits + p.bbits;
+  if (bits > 64) return false;
+  p.passes = (bits + kMaxDigitBits - 1) / kMaxDigitBits;
   if (p.passes < 1) p.passes = 1;
+  for (int i = 0, at = 0; i < p.passes; ++i) {  // spread the key bits evenly over the passes
+    const int w = (bits - at + (p.passes - i) - 1) / (p.passes - i);
+    p.shift[i] = at;
+    p.width[i] = w < 1 ? 1 : w;
+    at += w;
+  }
   p.sort_blocks = (uint32_t)((p.N + kSortTile - 1) / kSortTile);
   p.seg_blocks = (uint32_t)((p.N + kSegTile - 1) / kSegTile);
+  p.fused = p.sort_blocks <= (uint32_t)kFusedMaxTiles;
   size_t off = 0;
   for (int i = 0; i < 2; ++i) {
     p.off_key[i] = off;
@@ -285,8 +417,8 @@ bool plan_group(int64_t T, int k, int E, int L, int r, GroupPlan* plan) {
     p.off_idx[i] = off;
     off = align256(off + (size_t)p.N * 4);
   }
-  p.off_hist = off;
-  off = align256(off + (size_t)kBins * p.sort_blocks * 4);
+  p.off_table = off;
+  off = align256(off + (size_t)kGroupBins * p.sort_blocks * 4);
   p.off_blocksum = off;
   off = align256(off + ((size_t)p.seg_blocks + 1) * 4);
   p.total_bytes = off;
@@ -300,9 +432,10 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
   const uint32_t N = (uint32_t)plan.N;
   uint64_t* keybuf[2] = {(uint64_t*)(ws + plan.off_key[0]), (uint64_t*)(ws + plan.off_key[1])};
   int32_t* idxbuf[2] = {(int32_t*)(ws + plan.off_idx[0]), (int32_t*)(ws + plan.off_idx[1])};
-  uint32_t* hist = (uint32_t*)(ws + plan.off_hist);
+  uint32_t* table = (uint32_t*)(ws + plan.off_table);
   uint32_t* blocksum = (uint32_t*)(ws + plan.off_blocksum);
   const uint32_t nblk = plan.sort_blocks;
+  const dim3 grid(nblk), block(kSortThreads);
 
   KeySource src{expert, bucket, nullptr, nullptr, (uint32_t)k, (uint32_t)E, plan.bbits};
   const uint64_t* sorted_key = nullptr;
@@ -310,27 +443,46 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     const bool last = p == plan.passes - 1;
     uint64_t* dkey = keybuf[p & 1];
     int32_t* didx = last ? perm : idxbuf[p & 1];
-    const int shift = 8 * p;
-    if (p == 0) {
-      hipLaunchKernelGGL(sort_hist_kernel<true>, dim3(nblk), dim3(kSortThreads), 0, stream, src, N, shift, nblk, hist);
-      hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, hist, (uint32_t)kBins * nblk);
-      hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3(nblk), dim3(kSortThreads), 0, stream, src, N, shift, nblk,
-                         hist, dkey, didx);
+    PassArgs a{};
+    a.shift = plan.shift[p];
+    a.mask = (1u << plan.width[p]) - 1u;
+    a.nblk = nblk;
+    a.table = table;
+    hipError_t e = hipSuccess;
+    if (plan.fused) {
+      if (p == 0) {
+        hipLaunchKernelGGL((sort_hist_kernel<true, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+        e = launch_scatter<true, true>(src, N, a, dkey, didx, stream);
+      } else {
+        hipLaunchKernelGGL((sort_hist_kernel<false, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+        e = launch_scatter<false, true>(src, N, a, dkey, didx, stream);
+      }
     } else {
-      hipLaunchKernelGGL(sort_hist_kernel<false>, dim3(nblk), dim3(kSortThreads), 0, stream, src, N, shift, nblk, hist);
-      hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, hist, (uint32_t)kBins * nblk);
-      hipLaunchKernelGGL(sort_scatter_kernel<false>, dim3(nblk), dim3(kSortThreads), 0, stream, src, N, shift, nblk,
-                         hist, dkey, didx);
+      if (p == 0)
+        hipLaunchKernelGGL((sort_hist_kernel<true, false>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+      else
+        hipLaunchKernelGGL((sort_hist_kernel<false, false>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+      hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, table, (a.mask + 1u) * nblk);
+      e = p == 0 ? launch_scatter<true, false>(src, N, a, dkey, didx, stream)
+                 : launch_scatter<false, false>(src, N, a, dkey, didx, stream);
     }
+    if (e != hipSuccess) return e;
     src.key = dkey;
     src.idx = didx;
     sorted_key = dkey;
   }
   const uint32_t sblk = plan.seg_blocks;
   hipLaunchKernelGGL(seg_count_kernel, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, N, sblk, blocksum);
-  hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, blocksum, sblk + 1);
-  hipLaunchKernelGGL(seg_write_kernel, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, perm, N, (uint32_t)E,
-                     plan.bbits, blocksum, seg_offsets, seg_expert, expert_offsets, seg_of, num_segments);
+  if (sblk <= (uint32_t)kSelfPrefixMaxTiles) {
+    hipLaunchKernelGGL(seg_write_kernel<true>, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, perm, N,
+                       (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert, expert_offsets, seg_of,
+                       num_segments);
+  } else {
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, blocksum, sblk + 1);
+    hipLaunchKernelGGL(seg_write_kernel<false>, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, perm, N,
+                       (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert, expert_offsets, seg_of,
+                       num_segments);
+  }
   return hipGetLastError();
 }
 

@@ -14,17 +14,24 @@ hipError_t launch_hash(const void* tokens, const void* rot, int64_t T, int d, in
                        uint64_t* bucket, hipStream_t stream);
 
 // ---- step 2: group ------------------------------------------------------
+constexpr int kSortTile = 2048;            // assignments per sort tile
+constexpr int kSegTile = 1024;             // sorted positions per cluster-numbering tile
+constexpr int kMaxDigitBits = 9;           // radix digit width limit
+constexpr int kGroupBins = 1 << kMaxDigitBits;
+constexpr int kFusedMaxTiles = 256;        // up to this many sort tiles: no scan launch
+constexpr int kSelfPrefixMaxTiles = 4096;  // up to this many numbering tiles: no scan launch
+
 struct GroupPlan {
   int64_t N;
   int ebits, bbits;      // key = expert << bbits | bucket
-  int passes;            // 8-bit radix passes over ebits + bbits key bits
+  int passes;            // radix passes over ebits + bbits key bits
+  int shift[8], width[8];  // digit of pass p is (key >> shift[p]) & ((1 << width[p]) - 1)
+  bool fused;            // scatter blocks derive their offsets themselves (small inputs)
   uint32_t sort_blocks;  // tiles of kSortTile assignments
   uint32_t seg_blocks;   // tiles of kSegTile sorted positions
   // byte offsets into the workspace
-  size_t off_key[2], off_idx[2], off_hist, off_blocksum, total_bytes;
+  size_t off_key[2], off_idx[2], off_table, off_blocksum, total_bytes;
 };
-constexpr int kSortTile = 2048;
-constexpr int kSegTile = 1024;
 
 // Fills the plan; returns false when ebits + bbits > 64.
 bool plan_group(int64_t T, int k, int E, int L, int r, GroupPlan* plan);

@@ -84,6 +84,15 @@ def test_shapes(H, dtype, T, d, k, E, L, r):
     H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn)
 
 
+def test_large_inputs_take_the_histogram_scan_scatter_route(H):
+    # more than 256 sort tiles: per-pass histogram + table scan + scatter kernels
+    tokens, rot, expert = _rand_inputs(41, 280000, 8, 2, 3, 2, 4, "bf16", centers=5000)
+    H.run_and_check(tokens, rot, expert, 3, "bf16", _scale_fn)
+    # more than 4096 numbering tiles: scanned tile counts
+    tokens, rot, expert = _rand_inputs(42, 2150000, 8, 2, 2, 3, 2, "bf16", centers=3000)
+    H.run_and_check(tokens, rot, expert, 2, "bf16", _scale_fn)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_all_tokens_identical_one_cluster(H, dtype):
     T, d, E = 3000, 64, 1
