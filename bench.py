@@ -27,6 +27,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per restore_kernel launch from rocprofv3 --pmc (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, factors from
+# a 1 GiB calibration copy); figures and commands are kept in profiles/path_t5_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {("t5", "topk_logits"): 633.3e6}
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
@@ -77,6 +80,9 @@ def main():
     ap.add_argument("--gate", default=None, help="override the gate kind (e.g. 'content' for the supplementary run)")
     ap.add_argument("--copies", type=int, default=2, help="independent input copies rotated between steps")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the loop, run one plain device-to-device copy of this many MiB (a kernel of known "
+                         "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         _fail("bench.py: this path is single-GPU by construction (no collectives are built); run with --gpus 1")
@@ -132,6 +138,15 @@ def main():
         lsh.lshmoe_decompress(x, o.centroids, ecs[c], o.seg_of, o.seg_offsets, k, ys[c])
         if ev: ev[3].record()
 
+    if args.calibration_copy_mib > 0:
+        n_el = args.calibration_copy_mib * (1 << 20) // 4
+        src_buf = torch.ones(n_el, dtype=torch.float32, device="cuda")
+        dst_buf = torch.empty_like(src_buf)
+        torch.cuda.synchronize()
+        dst_buf.copy_(src_buf)          # reads and writes calibration_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src_buf, dst_buf
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -170,7 +185,7 @@ def main():
                    "single_member_segments": n_single, "input_copies_rotated": copies},
         "roofline": {"kernel": "restore_kernel (lshmoe_decompress)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes": restore_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.gate)), "algorithmic_bytes": restore_bytes,
                      "algorithmic_bytes_without_singleton_skip": restore_bytes_noskip,
                      "avg_launch_ms": float(dec_ms)},
         "stages_ms": {"hash": float(hash_ms), "compress": float(comp_ms), "decompress": float(dec_ms)},
