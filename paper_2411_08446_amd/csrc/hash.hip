@@ -60,8 +60,8 @@ constexpr int kSteps = 4;    // MFMA steps per chunk (two pieces, one per lane h
 
 __device__ __forceinline__ int swizzle(int row, int piece) { return piece ^ (row & 7); }
 
-template <typename DT, int MT, int NTK, int XDEPTH, bool ALIGNED8, bool KTAIL>
-__global__ __launch_bounds__(256) void hash_kernel(const char* __restrict__ tokens, const char* __restrict__ rot,
+template <typename DT, int MT, int NTK, int XDEPTH, int OCC, bool ALIGNED8, bool KTAIL>
+__global__ __launch_bounds__(256, OCC) void hash_kernel(const char* __restrict__ tokens, const char* __restrict__ rot,
                                                    uint64_t* __restrict__ bucket, uint32_t T, int row_pieces, int L,
                                                    int r, int hpg) {
   constexpr int RA = MT * 32;              // rows of R staged per chunk
@@ -177,51 +177,99 @@ __global__ __launch_bounds__(256) void hash_kernel(const char* __restrict__ toke
     for (int u = 0; u < NTK; ++u) {
       for (int lh = 0; lh < nh; ++lh) {
         const int lo = lh * r;
-        float best = -1.0f, bv = 0.0f;   // largest magnitude so far and the signed value that attains it
-        int bi = 0x7fffffff;
+        uint32_t best;   // bit pattern of the largest magnitude among this lane's rows of the hash
+        int bi;          // lowest row (relative to the hash) attaining it
+        bool neg;        // sign of the value there
+        if (ALIGNED8) {
+          // r and every hash boundary are multiples of 8: the four rows 8*jb + 4*h + (0..3) a lane holds of
+          // an 8-row block are inside the hash or outside it together, for every lane alike.
+          // Pass 1: binary32 patterns order like integers, so a signed-integer max finds the largest positive
+          // value and an unsigned max the largest-magnitude negative one (two 3-operand max chains).
+          int pmax = (int)0x80000000;
+          uint32_t nmax = 0;
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-          if (t * 32 + 31 < lo || t * 32 >= lo + r) continue;  // wave-uniform
-          if (ALIGNED8) {
-            // r and every hash boundary are multiples of 8: the four rows 8*jb + 4*h + (0..3) a lane holds
-            // of an 8-row block are inside the hash or outside it together, for every lane alike
+          for (int t = 0; t < MT; ++t) {
+            if (t * 32 + 31 < lo || t * 32 >= lo + r) continue;  // wave-uniform
 #pragma unroll
             for (int jb = 0; jb < 4; ++jb) {
               const int base = t * 32 + 8 * jb - lo;
               if (base < 0 || base >= r) continue;  // wave-uniform
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
-                const float v = acc[t][u][4 * jb + i];
-                const float av = fabsf(v);
-                if (av > best) {
-                  best = av;
-                  bi = base + 4 * h + i;
-                  bv = v;
+                const uint32_t vi = __float_as_uint(acc[t][u][4 * jb + i]);
+                pmax = max(pmax, (int)vi);
+                nmax = max(nmax, vi);
+              }
+            }
+          }
+          const uint32_t mp = pmax >= 0 ? (uint32_t)pmax : 0u;
+          const uint32_t mn = (nmax >> 31) ? (nmax & 0x7fffffffu) : 0u;
+          best = max(mp, mn);
+          neg = mn > mp;
+          // Pass 2: lowest row whose magnitude equals the maximum (descending, so the last hit is the lowest).
+          const float bestf = __uint_as_float(best);
+          bi = 0x7fffffff;
+#pragma unroll
+          for (int t = MT - 1; t >= 0; --t) {
+            if (t * 32 + 31 < lo || t * 32 >= lo + r) continue;
+#pragma unroll
+            for (int jb = 3; jb >= 0; --jb) {
+              const int base = t * 32 + 8 * jb - lo;
+              if (base < 0 || base >= r) continue;
+#pragma unroll
+              for (int i = 3; i >= 0; --i)
+                if (fabsf(acc[t][u][4 * jb + i]) == bestf) bi = base + 4 * h + i;
+            }
+          }
+          // +m and -m both present in this lane (exact tie in magnitude): the sign is that of the lowest row
+          if (__any(mp == mn && best != 0u)) {
+            uint32_t wbits = neg ? 0x80000000u : 0u;  // pattern of the value at the lowest such row
+#pragma unroll
+            for (int t = MT - 1; t >= 0; --t) {
+              if (t * 32 + 31 < lo || t * 32 >= lo + r) continue;
+#pragma unroll
+              for (int jb = 3; jb >= 0; --jb) {
+                const int base = t * 32 + 8 * jb - lo;
+                if (base < 0 || base >= r) continue;
+#pragma unroll
+                for (int i = 3; i >= 0; --i) {
+                  const float v = acc[t][u][4 * jb + i];
+                  if (fabsf(v) == bestf) wbits = __float_as_uint(v);
                 }
               }
             }
-          } else {
+            neg = (wbits >> 31) != 0u;
+          }
+        } else {
+          float bestf = -1.0f, bv = 0.0f;
+          bi = 0x7fffffff;
+#pragma unroll
+          for (int t = 0; t < MT; ++t) {
+            if (t * 32 + 31 < lo || t * 32 >= lo + r) continue;  // wave-uniform
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
               const int rel = t * 32 + 8 * (j >> 2) + 4 * h + (j & 3) - lo;  // ascending in j for a fixed lane
               const float v = acc[t][u][j];
               const float av = (unsigned)rel < (unsigned)r ? fabsf(v) : -2.0f;
-              if (av > best) {
-                best = av;
+              if (av > bestf) {
+                bestf = av;
                 bi = rel;
                 bv = v;
               }
             }
           }
+          best = bestf < 0.0f ? 0u : __float_as_uint(bestf);  // a lane may hold no row of this hash
+          neg = bv < 0.0f;
         }
-        const float obest = __shfl_xor(best, 32, 64);
+        // the other half of the token's rows sits in lane l ^ 32 (magnitude patterns compare as integers)
+        const uint32_t obest = (uint32_t)__shfl_xor((int)best, 32, 64);
         const int obi = __shfl_xor(bi, 32, 64);
-        const float obv = __shfl_xor(bv, 32, 64);
+        const int oneg = __shfl_xor((int)neg, 32, 64);
         if (obest > best || (obest == best && obi < bi)) {
           bi = obi;
-          bv = obv;
+          neg = oneg != 0;
         }
-        b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)(bi + (bv < 0.0f ? r : 0));
+        b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)(bi + (neg ? r : 0));
       }
     }
   }
@@ -234,13 +282,13 @@ __global__ __launch_bounds__(256) void hash_kernel(const char* __restrict__ toke
   }
 }
 
-template <typename DT, int MT, int NTK, int XDEPTH, bool ALIGNED8, bool KTAIL>
+template <typename DT, int MT, int NTK, int XDEPTH, int OCC, bool ALIGNED8, bool KTAIL>
 hipError_t launch_one(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
                       hipStream_t stream) {
   constexpr int kBlockTokens = 4 * NTK * 32;
   constexpr size_t lds_bytes = (size_t)2 * MT * 32 * kPieces * 16;
   static_assert(lds_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
-  auto kern = hash_kernel<DT, MT, NTK, XDEPTH, ALIGNED8, KTAIL>;
+  auto kern = hash_kernel<DT, MT, NTK, XDEPTH, OCC, ALIGNED8, KTAIL>;
   if (lds_bytes > 48 * 1024) {
     static bool raised = false;            // benign race: the attribute is idempotent
     if (!raised) {
@@ -266,15 +314,16 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
   auto R = (const char*)rot;
   // fast instance: r a multiple of 8 (uniform epilogue) and rows a whole number of 4 x 128-byte chunks (no k tail)
   const bool fast = r % 8 == 0 && row_pieces % (kPieces * 4) == 0;
-#define LSHMOE_HASH(MT, NTK, XD)                                                                      \
-  (fast ? launch_one<DT, MT, NTK, XD, true, false>(x, R, bucket, T, row_pieces, L, r, hpg, stream)    \
-        : launch_one<DT, MT, NTK, XD, false, true>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
-  if (mt <= 1) return LSHMOE_HASH(1, 1, 4);
-  if (mt == 2) return LSHMOE_HASH(2, 1, 4);
-  if (mt == 3) return LSHMOE_HASH(3, 1, 4);
-  if (mt == 4) return LSHMOE_HASH(4, 1, 4);
-  if (mt <= 6) return LSHMOE_HASH(6, 2, 2);
-  return LSHMOE_HASH(8, 2, 2);
+#define LSHMOE_HASH(MT, NTK, XD, OCC)                                                                      \
+  (fast ? launch_one<DT, MT, NTK, XD, OCC, true, false>(x, R, bucket, T, row_pieces, L, r, hpg, stream)    \
+        : launch_one<DT, MT, NTK, XD, OCC, false, true>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
+  // OCC workgroups share a compute unit: while one waits at its chunk barrier the other issues MFMAs
+  if (mt <= 1) return LSHMOE_HASH(1, 1, 4, 2);
+  if (mt == 2) return LSHMOE_HASH(2, 1, 4, 2);
+  if (mt == 3) return LSHMOE_HASH(3, 1, 4, 2);
+  if (mt == 4) return LSHMOE_HASH(4, 1, 4, 2);
+  if (mt <= 6) return LSHMOE_HASH(6, 1, 2, 2);
+  return LSHMOE_HASH(8, 1, 2, 2);
 #undef LSHMOE_HASH
 }
 

@@ -136,6 +136,29 @@ def test_zero_tokens_and_exact_ties(H):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_ties_on_the_fast_hash_instance(H, dtype):
+    # rows of 4 x 128 bytes and r a multiple of 8 select the fast kernel instance; +m / -m ties inside one lane's
+    # rows (rows 1 and 2 of a tile sit in the same lane) and across the two lane halves (rows 2 and 5)
+    d = 256 if dtype == "bf16" else 128
+    r, L = 8, 2
+    rot = np.zeros((L, r, d), np.float32)
+    rot[0, np.arange(r), np.arange(r)] = 1.0
+    rot[1, np.arange(r), np.arange(r) + 8] = 1.0
+    x = np.zeros((8, d), np.float32)
+    x[0, 1] = -3.0; x[0, 2] = 3.0            # same lane, lowest row negative -> code 1 + r
+    x[1, 1] = 3.0; x[1, 2] = -3.0            # same lane, lowest row positive -> code 1
+    x[2, 2] = 3.0; x[2, 5] = -3.0            # different lane halves -> code 2
+    x[3, 2] = -3.0; x[3, 5] = 3.0            # -> code 2 + r
+    x[4, 8 + 6] = -1.0; x[4, 8 + 7] = 1.0; x[4, 8 + 3] = 1.0   # second hash: three-way tie -> row 3, positive
+    x[5, :] = 0.0                            # zero token
+    x[6, 0:8] = -2.0                         # all rows tie, all negative -> 0 + r
+    x[7, 4] = -0.0                           # negative zero counts as positive
+    expert = np.zeros((8, 1), np.int32)
+    run = H.run_and_check(synth.f32_to_storage(x, dtype), synth.f32_to_storage(rot, dtype), expert, 1, dtype, _scale_fn)
+    assert run.bucket.tolist() == [9 * 16, 1 * 16, 2 * 16, 10 * 16, 3, 0, 8 * 16, 0]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_no_residual_flag_and_without_seg_offsets(H, dtype):
     tokens, rot, expert = _rand_inputs(9, 900, 32, 2, 6, 2, 8, dtype, centers=30)
     H.run_and_check(tokens, rot, expert, 6, dtype, _scale_fn, flags=H.lsh.LSHMOE_FLAG_NO_RESIDUAL)
