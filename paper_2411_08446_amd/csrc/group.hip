@@ -31,6 +31,7 @@ constexpr int kSortThreads = 256;
 constexpr int kSortItems = kSortTile / kSortThreads;  // 8
 constexpr int kGroupsPerTile = kSortTile / kWave;     // 32 waves' worth of keys
 constexpr int kGhStride = kGroupsPerTile + 1;          // per-bin row of group counts, padded against bank conflicts
+constexpr int kTableBatch = 32;                        // count-table rows a thread fetches per round trip
 constexpr int kSegThreads = 256;
 constexpr int kSegItems = kSegTile / kSegThreads;     // 4
 
@@ -168,8 +169,6 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource sr
   extern __shared__ uint32_t gh[];  // [kGroupBins][kGhStride] per-bin counts of each 64-key group, then start offsets
   __shared__ uint32_t wave_sum[4];
   __shared__ uint32_t part[2][2][kGroupBins];  // FUSED: [before/total][tile parity][bin]
-  for (int i = threadIdx.x; i < kGroupBins * kGhStride; i += kSortThreads) gh[i] = 0;
-  __syncthreads();
   const uint32_t base = blockIdx.x * kSortTile;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
@@ -181,6 +180,42 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource sr
 #pragma unroll
   for (int it = 0; it < kSortItems; ++it)
     load_item<FIRST>(src, min(base + it * kSortThreads + threadIdx.x, N - 1), key[it], idx[it]);
+  static_assert((kGroupBins * kGhStride) % 4 == 0, "gh is cleared 16 bytes at a time");
+  for (int i = threadIdx.x; i < kGroupBins * kGhStride / 4; i += kSortThreads)  // while the loads fly
+    reinterpret_cast<uint4*>(gh)[i] = make_uint4(0, 0, 0, 0);
+  if (FUSED) {
+    // counts[tile][bin]: keys of bin b in earlier tiles come first, after all keys of smaller bins
+    // Threads 0..127 walk the even tiles' rows, threads 128..255 the odd ones, four bins (16 bytes) each,
+    // in batches of independent loads; the two parities are then combined through LDS.
+    {
+      const uint32_t parity = threadIdx.x >> 7, b4 = (threadIdx.x & 127) * 4;
+      uint32_t bef[4] = {0, 0, 0, 0}, tot[4] = {0, 0, 0, 0};
+      for (uint32_t t0 = parity; t0 < a.nblk; t0 += 2 * kTableBatch) {
+        uint4 v[kTableBatch];
+#pragma unroll
+        for (int q = 0; q < kTableBatch; ++q) {
+          const uint32_t t = t0 + 2 * q;
+          v[q] = t < a.nblk ? *reinterpret_cast<const uint4*>(a.table + t * kGroupBins + b4) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < kTableBatch; ++q) {
+          const bool earlier = t0 + 2 * q < blockIdx.x;
+          const uint32_t w[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            tot[j] += w[j];
+            bef[j] += earlier ? w[j] : 0u;
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        part[0][parity][b4 + j] = bef[j];
+        part[1][parity][b4 + j] = tot[j];
+      }
+    }
+  }
+  __syncthreads();
 #pragma unroll
   for (int it = 0; it < kSortItems; ++it) {
     const uint32_t i = base + it * kSortThreads + threadIdx.x;
@@ -200,36 +235,6 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource sr
   // first output position of each bin for this tile
   uint32_t start[2];
   if (FUSED) {
-    // counts[tile][bin]: keys of bin b in earlier tiles come first, after all keys of smaller bins
-    // Threads 0..127 walk the even tiles' rows, threads 128..255 the odd ones, four bins (16 bytes) each,
-    // in batches of independent loads; the two parities are then combined through LDS.
-    {
-      const uint32_t parity = threadIdx.x >> 7, b4 = (threadIdx.x & 127) * 4;
-      uint32_t bef[4] = {0, 0, 0, 0}, tot[4] = {0, 0, 0, 0};
-      for (uint32_t t0 = parity; t0 < a.nblk; t0 += 32) {
-        uint4 v[16];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const uint32_t t = t0 + 2 * q;
-          v[q] = t < a.nblk ? *reinterpret_cast<const uint4*>(a.table + t * kGroupBins + b4) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const bool earlier = t0 + 2 * q < blockIdx.x;
-          const uint32_t w[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            tot[j] += w[j];
-            bef[j] += earlier ? w[j] : 0u;
-          }
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        part[0][parity][b4 + j] = bef[j];
-        part[1][parity][b4 + j] = tot[j];
-      }
-    }
     __syncthreads();
     uint32_t before[2], total[2];
 #pragma unroll
