@@ -8,7 +8,7 @@
 // over a lane's own registers plus one exchange with lane l^32; the rotated
 // vectors are never written to memory.
 //
-// Tiling.  A workgroup of 4 waves owns 4*NTK*32 tokens and all rows of one
+// Tiling.  A workgroup of WAVES waves owns WAVES*NTK*32 tokens and all rows of one
 // "hash group" (as many whole hashes as fit in 256 rows of R).  Each wave
 // keeps MT x NTK accumulator tiles (all rows, its own NTK*32 tokens), so a
 // token's bucket id is completed inside one wave.  k is walked in chunks of
@@ -19,7 +19,7 @@
 //     into registers, XDEPTH-1 chunks ahead of use; measured on MI355X this
 //     access streams as fast as a fully coalesced read, so the tokens - the
 //     only HBM traffic of the kernel - never touch LDS.
-//   R (A operand): shared by the 4 waves, so each 128-byte chunk of the
+//   R (A operand): shared by the waves, so each 128-byte chunk of the
 //     group's rows is staged in LDS (double buffered; the next chunk's global
 //     loads are in flight during the MFMAs of the current one).  The rows sit
 //     in LDS with an XOR swizzle of the 16-byte piece index by the row so
@@ -60,8 +60,8 @@ constexpr int kSteps = 4;    // MFMA steps per chunk (two pieces, one per lane h
 
 __device__ __forceinline__ int swizzle(int row, int piece) { return piece ^ (row & 7); }
 
-template <typename DT, int MT, int NTK, int XDEPTH, int OCC, bool ALIGNED8, bool KTAIL>
-__global__ __launch_bounds__(256, OCC) void hash_kernel(const char* __restrict__ tokens, const char* __restrict__ rot,
+template <typename DT, int MT, int NTK, int XDEPTH, int WAVES, int OCC, bool ALIGNED8, bool KTAIL>
+__global__ __launch_bounds__(WAVES * 64, OCC) void hash_kernel(const char* __restrict__ tokens, const char* __restrict__ rot,
                                                    uint64_t* __restrict__ bucket, uint32_t T, int row_pieces, int L,
                                                    int r, int hpg) {
   constexpr int RA = MT * 32;              // rows of R staged per chunk
@@ -69,14 +69,18 @@ __global__ __launch_bounds__(256, OCC) void hash_kernel(const char* __restrict__
   extern __shared__ uint4 lds[];           // [2][SLOTS]
 
   const int tid = threadIdx.x;
-  __builtin_assume(tid >= 0 && tid < 256);
+  constexpr int TH = WAVES * 64;           // threads of the workgroup
+  constexpr int RS = TH / kPieces;         // rows of R one staging sweep of the workgroup covers
+  constexpr int LA = RA / RS;              // staging loads per thread and chunk
+  static_assert(RA % RS == 0, "the rows of R must be a whole number of staging sweeps");
+  __builtin_assume(tid >= 0 && tid < TH);
   const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
   const uint32_t row_bytes = (uint32_t)row_pieces * 16u;
   const int nchunks = ((row_pieces + kPieces - 1) / kPieces + XDEPTH - 1) / XDEPTH * XDEPTH;
 
   // token rows of this lane (rows past the last token re-read it; their ids are never stored)
-  const uint32_t tok_wave = (blockIdx.x * 4u + wave) * (uint32_t)(NTK * 32);
+  const uint32_t tok_wave = (blockIdx.x * (uint32_t)WAVES + wave) * (uint32_t)(NTK * 32);
   const char* xrow[NTK];
 #pragma unroll
   for (int u = 0; u < NTK; ++u)
@@ -97,22 +101,22 @@ __global__ __launch_bounds__(256, OCC) void hash_kernel(const char* __restrict__
     const int nh = min(hpg, L - l0);
     const int rows = nh * r;               // valid rows of R in this group (<= RA); rows past them repeat the last
     const char* rot_group = rot + (size_t)l0 * r * row_bytes;
-    uint32_t off_a[MT];
+    uint32_t off_a[LA];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) off_a[i] = (uint32_t)min(r0 + i * 32, rows - 1) * row_bytes + lp * 16;
+    for (int i = 0; i < LA; ++i) off_a[i] = (uint32_t)min(r0 + i * RS, rows - 1) * row_bytes + lp * 16;
 
-    uint4 stage[MT];
+    uint4 stage[LA];
     auto load_r = [&](int chunk) {
       const bool in_row = !KTAIL || chunk * kPieces + lp < row_pieces;   // the k tail is zero filled
       const char* a_base = rot_group + (size_t)chunk * (kPieces * 16);
 #pragma unroll
-      for (int i = 0; i < MT; ++i)
+      for (int i = 0; i < LA; ++i)
         stage[i] = in_row ? *reinterpret_cast<const uint4*>(a_base + off_a[i]) : make_uint4(0, 0, 0, 0);
     };
     auto store_r = [&](int buf) {
       uint4* dst = lds + buf * SLOTS + st_slot;
 #pragma unroll
-      for (int i = 0; i < MT; ++i) dst[i * 256] = stage[i];
+      for (int i = 0; i < LA; ++i) dst[i * TH] = stage[i];
     };
     uint4 xr[XDEPTH][NTK][kSteps];
     auto load_x = [&](int chunk, uint4 (&dst)[NTK][kSteps]) {
@@ -282,13 +286,13 @@ __global__ __launch_bounds__(256, OCC) void hash_kernel(const char* __restrict__
   }
 }
 
-template <typename DT, int MT, int NTK, int XDEPTH, int OCC, bool ALIGNED8, bool KTAIL>
+template <typename DT, int MT, int NTK, int XDEPTH, int WAVES, int OCC, bool ALIGNED8, bool KTAIL>
 hipError_t launch_one(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
                       hipStream_t stream) {
-  constexpr int kBlockTokens = 4 * NTK * 32;
+  constexpr int kBlockTokens = WAVES * NTK * 32;
   constexpr size_t lds_bytes = (size_t)2 * MT * 32 * kPieces * 16;
   static_assert(lds_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
-  auto kern = hash_kernel<DT, MT, NTK, XDEPTH, OCC, ALIGNED8, KTAIL>;
+  auto kern = hash_kernel<DT, MT, NTK, XDEPTH, WAVES, OCC, ALIGNED8, KTAIL>;
   if (lds_bytes > 48 * 1024) {
     static bool raised = false;            // benign race: the attribute is idempotent
     if (!raised) {
@@ -297,7 +301,7 @@ hipError_t launch_one(const char* x, const char* R, uint64_t* bucket, int64_t T,
       raised = true;
     }
   }
-  const dim3 grid((uint32_t)((T + kBlockTokens - 1) / kBlockTokens)), block(256);
+  const dim3 grid((uint32_t)((T + kBlockTokens - 1) / kBlockTokens)), block(WAVES * 64);
   hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg);
   return hipGetLastError();
 }
@@ -314,16 +318,27 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
   auto R = (const char*)rot;
   // fast instance: r a multiple of 8 (uniform epilogue) and rows a whole number of 4 x 128-byte chunks (no k tail)
   const bool fast = r % 8 == 0 && row_pieces % (kPieces * 4) == 0;
-#define LSHMOE_HASH(MT, NTK, XD, OCC)                                                                      \
-  (fast ? launch_one<DT, MT, NTK, XD, OCC, true, false>(x, R, bucket, T, row_pieces, L, r, hpg, stream)    \
-        : launch_one<DT, MT, NTK, XD, OCC, false, true>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
-  // OCC workgroups share a compute unit: while one waits at its chunk barrier the other issues MFMAs
-  if (mt <= 1) return LSHMOE_HASH(1, 1, 4, 2);
-  if (mt == 2) return LSHMOE_HASH(2, 1, 4, 2);
-  if (mt == 3) return LSHMOE_HASH(3, 1, 4, 2);
-  if (mt == 4) return LSHMOE_HASH(4, 1, 4, 2);
-  if (mt <= 6) return LSHMOE_HASH(6, 1, 2, 2);
-  return LSHMOE_HASH(8, 1, 2, 2);
+#define LSHMOE_HASH(MT, NTK, XD, WAVES, OCC)                                                                      \
+  (fast ? launch_one<DT, MT, NTK, XD, WAVES, OCC, true, false>(x, R, bucket, T, row_pieces, L, r, hpg, stream)    \
+        : launch_one<DT, MT, NTK, XD, WAVES, OCC, false, true>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
+  // Workgroup size.  Few rows of R: the kernel is bound by streaming the tokens, so the workgroups are made
+  // small enough that at least 512 of them exist (2 per compute unit).  Many rows of R (mt >= 6): the LDS
+  // staging of R dominates, and 8 waves sharing one staged copy beat two 4-wave workgroups with one each.
+  // OCC: waves per SIMD the register budget is cut for - while one wave waits at a chunk barrier another
+  // issues MFMAs.
+  if (mt >= 6) {
+    const bool wide = T >= 256 * 256;
+    if (mt == 6) return wide ? LSHMOE_HASH(6, 1, 2, 8, 1) : LSHMOE_HASH(6, 1, 2, 4, 2);
+    return wide ? LSHMOE_HASH(8, 1, 2, 8, 1) : LSHMOE_HASH(8, 1, 2, 4, 2);
+  }
+  const int waves = T >= 512 * 128 ? 4 : T >= 512 * 64 ? 2 : 1;
+#define LSHMOE_HASH_SMALL(MT)                                       \
+  (waves == 4 ? LSHMOE_HASH(MT, 1, 4, 4, 2) : waves == 2 ? LSHMOE_HASH(MT, 1, 4, 2, 2) : LSHMOE_HASH(MT, 1, 4, 1, 2))
+  if (mt <= 1) return LSHMOE_HASH_SMALL(1);
+  if (mt == 2) return LSHMOE_HASH_SMALL(2);
+  if (mt == 3) return LSHMOE_HASH_SMALL(3);
+  return LSHMOE_HASH_SMALL(4);
+#undef LSHMOE_HASH_SMALL
 #undef LSHMOE_HASH
 }
 
