@@ -364,6 +364,170 @@ __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Tiny inputs (N <= kSmallMaxN): the whole grouping in ONE workgroup of 16 waves and one launch.  With a
+// few thousand keys every multi-launch scheme is dominated by launch and drain latency (~4 us per kernel)
+// and one compute unit sorts them faster than the launches alone would take (measured: 24 us instead of
+// 38 us for compress at N = 2048; from about 16k keys on the single compute unit is the slower route).
+// Each wave owns a contiguous slice of the array.  Per pass: count digits per (wave, bin) with LDS atomics,
+// turn the counts into start offsets in (bin, wave) order, then walk the slice again 64 keys at a time:
+// a key's position is the running offset of its (wave, bin) plus its rank among the equal digits of its
+// round (wave ballots).  Slices and rounds follow element order, so the sort is stable.
+struct SmallArgs {
+  int passes, bbits;
+  int shift[8], width[8];
+  uint32_t N, E;
+  uint64_t* keybuf[2];
+  int32_t* idxbuf[2];
+  int32_t *seg_offsets, *seg_expert, *expert_offsets, *perm, *seg_of, *num_segments;
+};
+
+constexpr int kSmallWaves = 16;
+
+__device__ __forceinline__ uint32_t block_exclusive_scan_1024(uint32_t v, uint32_t* wave_sum /*[16]*/, uint32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wave_sum[wave] = inc;
+  __syncthreads();
+  uint32_t before = 0;
+  total = 0;
+#pragma unroll
+  for (int w = 0; w < kSmallWaves; ++w) {
+    if (w < wave) before += wave_sum[w];
+    total += wave_sum[w];
+  }
+  __syncthreads();
+  return before + inc - v;
+}
+
+__global__ __launch_bounds__(kSmallWaves * 64) void small_group_kernel(KeySource src, SmallArgs a) {
+  __shared__ uint32_t cnt[kSmallWaves][kGroupBins];  // 32 KB
+  __shared__ uint32_t wave_sum[kSmallWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const uint32_t N = a.N;
+  const uint32_t slice = ((N + kSmallWaves - 1) / kSmallWaves + 63u) & ~63u;  // keys per wave, whole rounds
+  const uint32_t lo = min((uint32_t)wave * slice, N), hi = min(lo + slice, N);
+
+  for (int p = 0; p < a.passes; ++p) {
+    const bool first = p == 0, last = p == a.passes - 1;
+    const int shift = a.shift[p];
+    const uint32_t mask = (1u << a.width[p]) - 1u;
+    KeySource from = src;
+    from.key = a.keybuf[(p + 1) & 1];
+    from.idx = a.idxbuf[(p + 1) & 1];
+    uint64_t* dkey = a.keybuf[p & 1];
+    int32_t* didx = last ? a.perm : a.idxbuf[p & 1];
+    auto load = [&](uint32_t i, uint64_t& key, int32_t& idx) {
+      if (first) load_item<true>(from, i, key, idx);
+      else load_item<false>(from, i, key, idx);
+    };
+
+    for (int i = threadIdx.x; i < kSmallWaves * kGroupBins; i += kSmallWaves * 64) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    for (uint32_t base = lo; base < hi; base += 256) {  // four rounds of loads in flight
+      uint64_t key[4];
+      int32_t idx[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) load(min(base + q * 64 + lane, N - 1), key[q], idx[q]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (base + q * 64 + lane < hi) atomicAdd(&cnt[wave][(uint32_t)(key[q] >> shift) & mask], 1u);
+    }
+    __syncthreads();
+    {  // counts -> start offsets, ordered by (bin, wave)
+      uint32_t c[kSmallWaves], tot = 0;
+      const bool owner = threadIdx.x < kGroupBins;
+#pragma unroll
+      for (int w = 0; w < kSmallWaves; ++w) {
+        c[w] = owner ? cnt[w][threadIdx.x] : 0u;
+        tot += c[w];
+      }
+      uint32_t unused;
+      uint32_t run = block_exclusive_scan_1024(tot, wave_sum, unused);
+      if (owner) {
+#pragma unroll
+        for (int w = 0; w < kSmallWaves; ++w) {
+          cnt[w][threadIdx.x] = run;
+          run += c[w];
+        }
+      }
+    }
+    __syncthreads();
+    {
+      uint64_t key;
+      int32_t idx;
+      if (lo < hi) load(min(lo + lane, N - 1), key, idx);
+      for (uint32_t base = lo; base < hi; base += 64) {
+        uint64_t nkey = 0;
+        int32_t nidx = 0;
+        if (base + 64 < hi) load(min(base + 64 + lane, N - 1), nkey, nidx);  // next round's keys fly meanwhile
+        const bool valid = base + lane < hi;
+        const uint32_t digit = (uint32_t)(key >> shift) & mask;
+        uint64_t same = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < kMaxDigitBits; ++b) {
+          const bool bit = (digit >> b) & 1u;
+          const uint64_t bal = __ballot(bit);
+          same &= bit ? bal : ~bal;
+        }
+        const uint32_t rank = (uint32_t)__popcll(same & lt_mask);
+        const uint32_t start = cnt[wave][digit];
+        if (valid) {
+          dkey[start + rank] = key;
+          didx[start + rank] = idx;
+          if (rank == 0) cnt[wave][digit] = start + (uint32_t)__popcll(same);  // after every lane of the round has read
+        }
+        key = nkey;
+        idx = nidx;
+      }
+    }
+    __syncthreads();  // the pass's global writes are visible to the whole workgroup (one compute unit, one L1)
+  }
+
+  // number the clusters: head flags over the sorted keys
+  const uint64_t* skey = a.keybuf[(a.passes - 1) & 1];
+  uint32_t heads = 0;
+  for (uint32_t base = lo; base < hi; base += 64) {
+    const uint32_t i = base + lane;
+    const bool head = i < hi && (i == 0 || skey[i] != skey[i - 1]);
+    heads += (uint32_t)__popcll(__ballot(head));
+  }
+  uint32_t total;
+  uint32_t seg_base = block_exclusive_scan_1024(lane == 0 ? heads : 0u, wave_sum, total);
+  seg_base = (uint32_t)__shfl((int)seg_base, 0, 64);  // lane 0 holds the heads before this wave's slice
+  for (uint32_t base = lo; base < hi; base += 64) {
+    const uint32_t i = base + lane;
+    const bool valid = i < hi;
+    const uint32_t ic = min(i, N - 1);  // lanes past the slice re-read a valid key (ic - 1 must not wrap when N == 1)
+    const uint64_t kcur = skey[ic], kprev = skey[ic == 0 ? 0u : ic - 1u];
+    const bool head = valid && (i == 0 || kcur != kprev);
+    const uint64_t hmask = __ballot(head);
+    const uint32_t seg = seg_base + (uint32_t)__popcll(hmask & (lt_mask | (1ull << lane))) - 1u;  // heads up to and including i
+    if (valid) {
+      const uint32_t e = (uint32_t)(kcur >> a.bbits);
+      if (head) {
+        a.seg_offsets[seg] = (int32_t)i;
+        a.seg_expert[seg] = (int32_t)e;
+        const uint32_t from_e = i == 0 ? 0u : (uint32_t)(kprev >> a.bbits) + 1u;
+        for (uint32_t x = from_e; x <= e; ++x) a.expert_offsets[x] = (int32_t)seg;  // experts that start (or are empty) here
+      }
+      a.seg_of[a.perm[i]] = (int32_t)seg;
+      if (i == N - 1) {
+        for (uint32_t x = e + 1; x <= a.E; ++x) a.expert_offsets[x] = (int32_t)(seg + 1);
+        a.seg_offsets[seg + 1] = (int32_t)N;
+        *a.num_segments = (int32_t)(seg + 1);
+      }
+    }
+    seg_base += (uint32_t)__popcll(hmask);
+  }
+}
+
 int bits_for(uint64_t max_value) {  // number of bits needed to hold max_value
   int b = 0;
   while (max_value) {
@@ -443,6 +607,23 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
   const dim3 grid(nblk), block(kSortThreads);
 
   KeySource src{expert, bucket, nullptr, nullptr, (uint32_t)k, (uint32_t)E, plan.bbits};
+  if (plan.N <= kSmallMaxN) {
+    SmallArgs a{};
+    a.passes = plan.passes;
+    a.bbits = plan.bbits;
+    for (int p = 0; p < plan.passes; ++p) {
+      a.shift[p] = plan.shift[p];
+      a.width[p] = plan.width[p];
+    }
+    a.N = N;
+    a.E = (uint32_t)E;
+    a.keybuf[0] = keybuf[0]; a.keybuf[1] = keybuf[1];
+    a.idxbuf[0] = idxbuf[0]; a.idxbuf[1] = idxbuf[1];
+    a.seg_offsets = seg_offsets; a.seg_expert = seg_expert; a.expert_offsets = expert_offsets;
+    a.perm = perm; a.seg_of = seg_of; a.num_segments = num_segments;
+    hipLaunchKernelGGL(small_group_kernel, dim3(1), dim3(kSmallWaves * 64), 0, stream, src, a);
+    return hipGetLastError();
+  }
   const uint64_t* sorted_key = nullptr;
   for (int p = 0; p < plan.passes; ++p) {
     const bool last = p == plan.passes - 1;

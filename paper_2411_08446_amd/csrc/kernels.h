@@ -20,6 +20,7 @@ constexpr int kMaxDigitBits = 9;           // radix digit width limit
 constexpr int kGroupBins = 1 << kMaxDigitBits;
 constexpr int kFusedMaxTiles = 256;        // up to this many sort tiles: no scan launch
 constexpr int kSelfPrefixMaxTiles = 4096;  // up to this many numbering tiles: no scan launch
+constexpr int kSmallMaxN = 4096;           // up to this many assignments: one workgroup, one launch
 
 struct GroupPlan {
   int64_t N;
