@@ -194,6 +194,22 @@ def main():
                       "frac": hash_flops / (hash_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype],
                       "token_read_gbs": T * row / (hash_ms * 1e-3) / 1e9},
     }
+    # supplementary (not part of `value`): the restore fused with the gate-weighted top-k combine, which
+    # writes one row per token instead of k
+    gw = torch.from_numpy(np.ascontiguousarray(w.gate_weight, dtype=np.float32)).cuda()
+    yc = torch.empty((T, d), dtype=tdt, device="cuda")
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(K, 50))]
+    for i, (e0, e1) in enumerate(ev):
+        c = i % copies
+        e0.record()
+        lsh.lshmoe_decompress_combine(xs[c], outs[c].centroids, ecs[c], outs[c].seg_of, outs[c].seg_offsets, gw, yc)
+        e1.record()
+    torch.cuda.synchronize()
+    comb_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev[5:]])) if len(ev) > 5 else None
+    comb_bytes = (S + T + n_multi_assign + n_multi_seg) * row + 8 * N + 4 * (S + 1)
+    result["supplementary_fused_combine"] = {
+        "decompress_combine_ms": comb_ms, "algorithmic_bytes": comb_bytes,
+        "achieved_gbs": comb_bytes / (comb_ms * 1e-3) / 1e9 if comb_ms else None}
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample)
     else:

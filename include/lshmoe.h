@@ -175,6 +175,29 @@ lshmoe_status lshmoe_decompress(const void* tokens, const void* centroids, const
                                 int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, uint32_t flags,
                                 void* out, void* stream);
 
+/*
+ * Restore fused with the gate-weighted combine of a token's k expert outputs
+ * (Eq. 2, with the gate values as weights; Eq. 4 and Eq. 5 for each term):
+ *     out[t, :] = sum_{j<k} gate_weight[t][j] *
+ *                 (expert_out[s_j, :] + (tokens[t, :] - centroids[s_j, :])),   s_j = seg_of[t*k + j],
+ * accumulated in binary32 in the order j = 0..k-1 and rounded once.  It writes
+ * one row per token instead of k and reads the token row once.  With
+ * LSHMOE_FLAG_NO_RESIDUAL the residual term is dropped.  The paper does not say
+ * whether its combine is weighted; pass weights of 1 for the unweighted sum of
+ * Eq. 2 as printed.
+ *
+ *   gate_weight [T, k]  in   binary32 (any values; they are not normalised here)
+ *   out         [T, d]  out  dtype
+ *   other arguments as for lshmoe_decompress.
+ *
+ * Errors: as for lshmoe_decompress; NULL gate_weight is LSHMOE_ERR_NULL.
+ */
+lshmoe_status lshmoe_decompress_combine(const void* tokens, const void* centroids, const void* expert_out,
+                                        const int32_t* seg_of, const int32_t* seg_offsets,
+                                        const float* gate_weight,
+                                        int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, uint32_t flags,
+                                        void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                     vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.lshmoe_decompress.restype = ctypes.c_int
     lib.lshmoe_decompress.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
+    lib.lshmoe_decompress_combine.restype = ctypes.c_int
+    lib.lshmoe_decompress_combine.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
     _lib = lib
     return lib
 
@@ -171,3 +173,19 @@ def lshmoe_decompress(tokens: torch.Tensor, centroids: torch.Tensor, expert_out:
     _check(load_library().lshmoe_decompress(
         _ptr(tokens), _ptr(centroids), _ptr(expert_out), _ptr(seg_of, torch.int32),
         _ptr(seg_offsets, torch.int32), T, d, k, _dtype_code(tokens), flags, _ptr(out), _stream(stream)))
+
+
+def lshmoe_decompress_combine(tokens: torch.Tensor, centroids: torch.Tensor, expert_out: torch.Tensor,
+                              seg_of: torch.Tensor, seg_offsets, gate_weight: torch.Tensor, out: torch.Tensor,
+                              flags: int = 0, stream=None) -> None:
+    """out [T, d] = sum_j gate_weight[t, j] * restored row of assignment (t, j)."""
+    T, d = tokens.shape
+    k = gate_weight.shape[1]
+    if gate_weight.shape[0] != T or seg_of.numel() != T * k or out.shape != (T, d) or out.dtype != tokens.dtype:
+        raise ValueError("gate_weight must be [T, k], seg_of N entries and out [T, d] of the token dtype")
+    if centroids.dtype != tokens.dtype or expert_out.dtype != tokens.dtype:
+        raise TypeError("centroids and expert_out must have the token dtype")
+    _check(load_library().lshmoe_decompress_combine(
+        _ptr(tokens), _ptr(centroids), _ptr(expert_out), _ptr(seg_of, torch.int32),
+        _ptr(seg_offsets, torch.int32), _ptr(gate_weight, torch.float32), T, d, k, _dtype_code(tokens), flags,
+        _ptr(out), _stream(stream)))

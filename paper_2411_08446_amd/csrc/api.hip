@@ -91,7 +91,7 @@ const char* lshmoe_status_string(int status) {
 
 const char* lshmoe_last_error(void) { return g_err; }
 
-int lshmoe_abi_version(void) { return 1; }
+int lshmoe_abi_version(void) { return 2; }
 
 lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E, int32_t L, int32_t r,
                                      lshmoe_dtype dtype, size_t* out_bytes) {
@@ -154,6 +154,24 @@ lshmoe_status lshmoe_decompress(const void* tokens, const void* centroids, const
   hipError_t e = lshmoe::launch_restore(tokens, centroids, expert_out, seg_of, seg_offsets, out, T * (int64_t)k, k, d,
                                         dtype == LSHMOE_BF16, flags, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("restore launch", e);
+  return ok();
+}
+
+lshmoe_status lshmoe_decompress_combine(const void* tokens, const void* centroids, const void* expert_out,
+                                        const int32_t* seg_of, const int32_t* seg_offsets, const float* gate_weight,
+                                        int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, uint32_t flags, void* out,
+                                        void* stream) {
+  if (!tokens || !centroids || !expert_out || !seg_of || !gate_weight || !out)
+    return fail(LSHMOE_ERR_NULL, "an input or output pointer is NULL");
+  if (T <= 0 || d <= 0 || k <= 0)
+    return fail(LSHMOE_ERR_SHAPE, "T, d, k must be positive (T=%lld, d=%d, k=%d)", (long long)T, d, k);
+  if (lshmoe_status st = check_row(d, (int)dtype)) return st;
+  if (flags & ~(uint32_t)LSHMOE_FLAG_NO_RESIDUAL) return fail(LSHMOE_ERR_UNSUPPORTED, "unknown flag bits 0x%x", flags);
+  if (T >= kMaxAssignments || T * (int64_t)k >= kMaxAssignments)
+    return fail(LSHMOE_ERR_UNSUPPORTED, "N = T*k = %lld assignments; the limit is 2^30 - 1", (long long)(T * (int64_t)k));
+  hipError_t e = lshmoe::launch_restore_combine(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, out, T,
+                                                k, d, dtype == LSHMOE_BF16, flags, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("restore-combine launch", e);
   return ok();
 }
 

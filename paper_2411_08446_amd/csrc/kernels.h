@@ -51,4 +51,8 @@ hipError_t launch_restore(const void* tokens, const void* centroids, const void*
                           const int32_t* seg_of, const int32_t* seg_offsets, void* out, int64_t N, int k, int d,
                           bool bf16, uint32_t flags, hipStream_t stream);
 
+hipError_t launch_restore_combine(const void* tokens, const void* centroids, const void* expert_out,
+                                  const int32_t* seg_of, const int32_t* seg_offsets, const float* gate_weight,
+                                  void* out, int64_t T, int k, int d, bool bf16, uint32_t flags, hipStream_t stream);
+
 }  // namespace lshmoe

@@ -80,6 +80,76 @@ __global__ __launch_bounds__(256) void restore_kernel(
   }
 }
 
+// Restore fused with the gate-weighted combine of the k expert outputs of a token (Eq. 2 with gate weights):
+//     out[t] = sum_j w[t][j] * (expert_out[s_j] + (tokens[t] - centroids[s_j])),   s_j = seg_of[t*k + j],
+// accumulated in binary32 in the order j = 0..k-1 and rounded once.  One lane group per token: the token row
+// is read once, and one row is written instead of k.
+template <typename DT, int LPR>
+__global__ __launch_bounds__(256) void restore_combine_kernel(
+    const char* __restrict__ tokens, const char* __restrict__ centroids, const char* __restrict__ expert_out,
+    const int32_t* __restrict__ seg_of, const int32_t* __restrict__ seg_offsets, const float* __restrict__ gate_weight,
+    char* __restrict__ out, uint32_t T, uint32_t k, uint32_t cpr, uint32_t flags) {
+  constexpr int G = 64 / LPR;
+  constexpr int E = Piece<DT>::kElems;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t t = ((blockIdx.x * 256u + threadIdx.x) >> 6) * G + lane / LPR;
+  if (t >= T) return;
+  const size_t row_bytes = (size_t)cpr * 16;
+  const bool no_res = (flags & 1u) != 0;
+  for (uint32_t c = lane % LPR; c < cpr; c += LPR) {
+    float acc[E], xv[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+    bool have_x = false;
+    for (uint32_t j = 0; j < k; ++j) {
+      const int32_t s = uniform<LPR>(seg_of[t * k + j]);
+      const float w = __int_as_float(uniform<LPR>(__float_as_int(gate_weight[t * k + j])));
+      bool full = !no_res;
+      if (full && seg_offsets != nullptr)
+        full = uniform<LPR>(seg_offsets[s + 1]) - uniform<LPR>(seg_offsets[s]) != 1;
+      float e[E];
+      Piece<DT>::widen(load16(expert_out + (size_t)s * row_bytes + c * 16), e);
+      if (full) {
+        if (!have_x) {
+          Piece<DT>::widen(load16(tokens + (size_t)t * row_bytes + c * 16), xv);
+          have_x = true;
+        }
+        float cv[E];
+        Piece<DT>::widen(load16(centroids + (size_t)s * row_bytes + c * 16), cv);
+#pragma unroll
+        for (int i = 0; i < E; ++i) e[i] += xv[i] - cv[i];
+      }
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] = fmaf(w, e[i], acc[i]);
+    }
+    store16_stream(out + (size_t)t * row_bytes + c * 16, Piece<DT>::narrow(acc));
+  }
+}
+
+template <typename DT, int LPR>
+void launch_combine_lpr(const void* tokens, const void* centroids, const void* expert_out, const int32_t* seg_of,
+                        const int32_t* seg_offsets, const float* gate_weight, void* out, int64_t T, int k,
+                        uint32_t cpr, uint32_t flags, hipStream_t stream) {
+  constexpr int G = 64 / LPR;
+  const uint64_t waves = ((uint64_t)T + G - 1) / G;
+  const uint32_t blocks = (uint32_t)((waves + 3) / 4);
+  hipLaunchKernelGGL((restore_combine_kernel<DT, LPR>), dim3(blocks), dim3(256), 0, stream, (const char*)tokens,
+                     (const char*)centroids, (const char*)expert_out, seg_of, seg_offsets, gate_weight, (char*)out,
+                     (uint32_t)T, (uint32_t)k, cpr, flags);
+}
+
+template <typename DT>
+void launch_combine_typed(const void* tokens, const void* centroids, const void* expert_out, const int32_t* seg_of,
+                          const int32_t* seg_offsets, const float* gate_weight, void* out, int64_t T, int k,
+                          uint32_t cpr, uint32_t flags, hipStream_t stream) {
+  if (cpr > 16)
+    launch_combine_lpr<DT, 64>(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, out, T, k, cpr, flags, stream);
+  else if (cpr > 4)
+    launch_combine_lpr<DT, 16>(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, out, T, k, cpr, flags, stream);
+  else
+    launch_combine_lpr<DT, 4>(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, out, T, k, cpr, flags, stream);
+}
+
 template <typename DT, int LPR>
 void launch_lpr(const void* tokens, const void* centroids, const void* expert_out, const int32_t* seg_of,
                 const int32_t* seg_offsets, void* out, int64_t N, int k, uint32_t cpr, uint32_t flags,
@@ -110,6 +180,17 @@ hipError_t launch_restore(const void* tokens, const void* centroids, const void*
   const uint32_t cpr = (uint32_t)((size_t)d * (bf16 ? 2 : 4) / 16);
   if (bf16) launch_typed<BF16>(tokens, centroids, expert_out, seg_of, seg_offsets, out, N, k, cpr, flags, stream);
   else launch_typed<F32>(tokens, centroids, expert_out, seg_of, seg_offsets, out, N, k, cpr, flags, stream);
+  return hipGetLastError();
+}
+
+hipError_t launch_restore_combine(const void* tokens, const void* centroids, const void* expert_out,
+                                  const int32_t* seg_of, const int32_t* seg_offsets, const float* gate_weight,
+                                  void* out, int64_t T, int k, int d, bool bf16, uint32_t flags, hipStream_t stream) {
+  const uint32_t cpr = (uint32_t)((size_t)d * (bf16 ? 2 : 4) / 16);
+  if (bf16)
+    launch_combine_typed<BF16>(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, out, T, k, cpr, flags, stream);
+  else
+    launch_combine_typed<F32>(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, out, T, k, cpr, flags, stream);
   return hipGetLastError();
 }
 

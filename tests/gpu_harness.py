@@ -127,3 +127,23 @@ def run_and_check(tokens: np.ndarray, rot: np.ndarray, expert: np.ndarray, E: in
         assert np.array_equal(oracle.widen(y_gpu[rows], dtype), oracle.widen(ec[g["seg_of"]][rows], dtype) + 0.0), \
             "one-member clusters must return the expert output exactly"
     return GpuRun(bucket, out, S, c_gpu, ec, y_gpu, flips)
+
+
+def check_combine(run: GpuRun, tokens: np.ndarray, gate_weight: np.ndarray, k: int, dtype: str, flags: int = 0,
+                  use_seg_offsets: bool = True):
+    """lshmoe_decompress_combine against the oracle's gate-weighted restore, on the clusters, centroids and
+    expert outputs of a finished run."""
+    T, d = tokens.shape
+    xt = to_device(tokens, dtype)
+    ect = torch.zeros_like(run.out.centroids)
+    ect[:run.S] = to_device(run.expert_out, dtype)
+    wt = torch.from_numpy(np.ascontiguousarray(gate_weight, dtype=np.float32)).cuda()
+    out = torch.full((T, d), float("nan"), dtype=xt.dtype, device="cuda")
+    lsh.lshmoe_decompress_combine(xt, run.out.centroids, ect, run.out.seg_of,
+                                  run.out.seg_offsets if use_seg_offsets else None, wt, out, flags=flags)
+    torch.cuda.synchronize()
+    got = to_storage(out, dtype)
+    seg_of = run.out.seg_of.cpu().numpy()
+    ref = oracle.restore_ref(tokens, run.centroids, run.expert_out, seg_of, k, dtype, no_residual=bool(flags & 1),
+                             gate_weight=gate_weight)
+    return assert_rows_close(got, ref, dtype, "restore+combine")

@@ -29,7 +29,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert {"lshmoe_hash", "lshmoe_compress", "lshmoe_decompress", "lshmoe_workspace_bytes",
+    assert {"lshmoe_hash", "lshmoe_compress", "lshmoe_decompress", "lshmoe_decompress_combine", "lshmoe_workspace_bytes",
             "lshmoe_status_string", "lshmoe_last_error", "lshmoe_abi_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -87,6 +87,9 @@ def test_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.lshmoe_decompress(p, p, p, p, None, 16, 64, 0, 1, 0, p, None) == lsh.LSHMOE_ERR_SHAPE
     assert lib.lshmoe_decompress(p, p, p, p, None, 16, 64, 1, 1, 2, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
     assert lib.lshmoe_decompress(p, p, p, p, None, 16, 63, 1, 0, 0, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
+    assert lib.lshmoe_decompress_combine(p, p, p, p, None, None, 16, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL
+    assert lib.lshmoe_decompress_combine(p, p, p, p, None, p, 16, 64, 2, 1, 4, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
+    assert lib.lshmoe_decompress_combine(p, p, p, p, None, p, 0, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_SHAPE
 
 
 def test_binding_refuses_host_tensors():

@@ -165,6 +165,28 @@ def test_no_residual_flag_and_without_seg_offsets(H, dtype):
     H.run_and_check(tokens, rot, expert, 6, dtype, _scale_fn, use_seg_offsets=False)
 
 
+@pytest.mark.parametrize("name,T", [("gpt", 3000), ("t5", 2200)])
+def test_fused_gate_weighted_combine_named(H, name, T):
+    cfg = synth.config(name, T=T, centers=120)
+    w = synth.generate(cfg)
+    run = H.run_and_check(w.tokens, w.rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
+    H.check_combine(run, w.tokens, w.gate_weight, cfg.k, cfg.dtype)
+    H.check_combine(run, w.tokens, w.gate_weight, cfg.k, cfg.dtype, flags=H.lsh.LSHMOE_FLAG_NO_RESIDUAL)
+    H.check_combine(run, w.tokens, w.gate_weight, cfg.k, cfg.dtype, use_seg_offsets=False)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,d,k,E", [(700, 24, 3, 5), (333, 512, 1, 4), (50, 8, 4, 4)])
+def test_fused_gate_weighted_combine_shapes(H, dtype, T, d, k, E):
+    tokens, rot, expert = _rand_inputs(77 + T, T, d, k, E, 2, 8, dtype, centers=max(2, T // 8))
+    gw = np.random.default_rng(T).random((T, k)).astype(np.float32) + 0.1
+    run = H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn)
+    H.check_combine(run, tokens, gw, k, dtype)
+    # weights of one reproduce the plain sum of the k restored rows
+    ones = np.ones((T, k), np.float32)
+    H.check_combine(run, tokens, ones, k, dtype)
+
+
 def test_deterministic_across_runs(H):
     cfg = synth.config("gpt", T=4000, centers=300)
     w = synth.generate(cfg)
