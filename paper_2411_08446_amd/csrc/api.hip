@@ -68,7 +68,7 @@ lshmoe_status check_compress_shape(int64_t T, int d, int k, int E, int L, int r,
     return fail(LSHMOE_ERR_UNSUPPORTED, "N = T*k = %lld assignments; the limit is 2^30 - 1", (long long)(T * (int64_t)k));
   if ((uint64_t)T * (uint64_t)k * ((size_t)d * item_size(dt) / 16) > 0xffffff00ull)
     return fail(LSHMOE_ERR_UNSUPPORTED, "N*d is too large for one launch");
-  if (!lshmoe::plan_group(T, k, E, L, r, plan))
+  if (!lshmoe::plan_group(T, d, k, E, L, r, plan))
     return fail(LSHMOE_ERR_UNSUPPORTED, "expert bits + bucket bits exceed 64 (E=%d, L=%d, r=%d)", E, L, r);
   return LSHMOE_OK;
 }
@@ -133,7 +133,9 @@ lshmoe_status lshmoe_compress(const void* tokens, const int32_t* expert, const u
   hipError_t e = lshmoe::launch_group(plan, expert, bucket, k, E, seg_offsets, seg_expert, expert_offsets, perm, seg_of,
                                       num_segments, (char*)workspace, s);
   if (e != hipSuccess) return hip_fail("group launch", e);
-  e = lshmoe::launch_centroid(tokens, perm, seg_offsets, num_segments, centroids, plan.N, k, d, dtype == LSHMOE_BF16, s);
+  e = lshmoe::launch_centroid(tokens, perm, seg_offsets, seg_of, num_segments, centroids,
+                              (float*)((char*)workspace + plan.off_partial),
+                              (uint32_t*)((char*)workspace + plan.off_counters), plan.N, k, d, dtype == LSHMOE_BF16, s);
   if (e != hipSuccess) return hip_fail("centroid launch", e);
   return ok();
 }

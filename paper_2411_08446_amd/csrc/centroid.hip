@@ -7,7 +7,9 @@
 // the row; with rows of 1 KB and more that is a whole wave per cluster, and
 // the cluster's offsets and member ids are wave-uniform scalars.  A one-member
 // cluster is a plain row copy.  Centroid rows are written with streaming
-// stores: nothing in this kernel reads them again.
+// stores: nothing in this kernel reads them again.  A cluster with more than
+// kCentroidWindow members is cut into windows that many waves sum side by
+// side; the wave that finishes last adds the window sums in position order.
 #include "kernels.h"
 
 namespace lshmoe {
@@ -20,66 +22,113 @@ template <int LPR> __device__ __forceinline__ int32_t uniform(int32_t v) {
   return LPR == 64 ? __builtin_amdgcn_readfirstlane(v) : v;  // a whole wave shares the value: keep it scalar
 }
 
-template <typename DT, int LPR>
-__global__ __launch_bounds__(256) void centroid_kernel(
-    const char* __restrict__ tokens, const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_offsets,
-    const int32_t* __restrict__ num_segments, char* __restrict__ centroids, uint32_t k, uint32_t cpr) {
-  constexpr int G = 64 / LPR;  // clusters handled side by side by one wave
+// Compensated sum of the token rows at sorted positions [a, b) (wave-wide, every lane takes pieces lane and
+// lane + 64 of each column group), written as binary32 to out_row.
+template <typename DT>
+__device__ __forceinline__ void window_sum(const char* __restrict__ tokens, const int32_t* __restrict__ perm,
+                                           int32_t a, int32_t b, uint32_t k, uint32_t cpr, size_t row_bytes,
+                                           float* __restrict__ out_row) {
   constexpr int E = Piece<DT>::kElems;
-  const uint32_t S = (uint32_t)*num_segments;
+  constexpr int kRows = 8;
   const uint32_t lane = threadIdx.x & 63;
-  const uint32_t s = ((blockIdx.x * 256u + threadIdx.x) >> 6) * G + lane / LPR;
-  if (s >= S) return;
-  const size_t row_bytes = (size_t)cpr * 16;
-  const int32_t lo = uniform<LPR>(seg_offsets[s]), hi = uniform<LPR>(seg_offsets[s + 1]);
-  const int32_t n = hi - lo;
-  const char* first = tokens + (size_t)((uint32_t)uniform<LPR>(perm[lo]) / k) * row_bytes;
-  char* dst = centroids + (size_t)s * row_bytes;
-  for (uint32_t c = lane % LPR; c < cpr; c += LPR) {
-    const uint4 v0 = load16(first + c * 16);
-    if (n == 1) {  // the mean of one row is the row
-      store16_stream(dst + c * 16, v0);
-      continue;
-    }
-    float acc[E], x[E];
-    Piece<DT>::widen(v0, acc);
-    int32_t p = lo + 1;
-    if (n <= kPlainSumMax) {
-      for (; p + 4 <= hi; p += 4) {
-        uint4 q[4];
+  for (uint32_t c0 = 0; c0 < cpr; c0 += 128) {
+    const uint32_t c[2] = {c0 + lane, c0 + 64 + lane};
+    float acc[2][E], comp[2][E];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-          q[u] = load16(tokens + (size_t)((uint32_t)uniform<LPR>(perm[p + u]) / k) * row_bytes + c * 16);
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          Piece<DT>::widen(q[u], x);
+      for (int i = 0; i < E; ++i) acc[h][i] = comp[h][i] = 0.0f;
+    for (int32_t p = a; p < b; p += kRows) {
+      uint4 q[kRows][2];
 #pragma unroll
-          for (int i = 0; i < E; ++i) acc[i] += x[i];
+      for (int u = 0; u < kRows; ++u) {
+        const int32_t pp = min(p + u, b - 1);  // the surplus rows of the last round are loaded and not added
+        const char* row = tokens + (size_t)((uint32_t)__builtin_amdgcn_readfirstlane(perm[pp]) / k) * row_bytes;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+          if (c[h] < cpr) q[u][h] = load16(row + c[h] * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < kRows; ++u) {
+        if (p + u < b) {
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            if (c[h] < cpr) {
+              float x[E];
+              Piece<DT>::widen(q[u][h], x);
+#pragma unroll
+              for (int i = 0; i < E; ++i) {
+                const float y = x[i] - comp[h][i];
+                const float t = acc[h][i] + y;
+                comp[h][i] = (t - acc[h][i]) - y;
+                acc[h][i] = t;
+              }
+            }
+          }
         }
       }
-      for (; p < hi; ++p) {
-        Piece<DT>::widen(load16(tokens + (size_t)((uint32_t)uniform<LPR>(perm[p]) / k) * row_bytes + c * 16), x);
+    }
 #pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] += x[i];
+    for (int h = 0; h < 2; ++h)
+      if (c[h] < cpr) {
+#pragma unroll
+        for (int i = 0; i < E; i += 4)
+          *(float4*)(out_row + (size_t)c[h] * E + i) = make_float4(acc[h][i], acc[h][i + 1], acc[h][i + 2], acc[h][i + 3]);
       }
-    } else {
-      // long cluster: compensated (Kahan) summation keeps the binary32 sum within
-      // a couple of ulps of the exact one however many members there are
-      float comp[E];
+  }
+}
+
+// A cluster with more than kCentroidWindow members is summed by several waves: the sorted positions are cut into
+// aligned blocks of kCentroidWindow; the wave that owns block m sums the part of the block that belongs to the
+// long cluster containing the block's first position (slot 2m) and the part that belongs to a long cluster
+// starting inside the block (slot 2m + 1; there is at most one, since a long cluster is longer than a block).
+// Every window bumps its cluster's counter; the wave that brings it to the cluster's window count adds the
+// partial sums in position order, so the result does not depend on which wave came last.
+template <typename DT>
+__device__ __forceinline__ void long_cluster_window(
+    const char* __restrict__ tokens, const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_offsets,
+    char* __restrict__ centroids, float* partial, uint32_t* counters, int32_t s, int32_t a, int32_t b, uint32_t slot,
+    uint32_t k, uint32_t cpr, uint32_t d) {
+  constexpr int E = Piece<DT>::kElems;
+  const size_t row_bytes = (size_t)cpr * 16;
+  const uint32_t lane = threadIdx.x & 63;
+  const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[s]);
+  const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[s + 1]);
+  window_sum<DT>(tokens, perm, a, b, k, cpr, row_bytes, partial + (size_t)slot * d);
+  const uint32_t m0 = (uint32_t)lo / kCentroidWindow, m1 = (uint32_t)(hi - 1) / kCentroidWindow;
+  const uint32_t first_slot = 2 * m0 + ((uint32_t)lo % kCentroidWindow != 0 ? 1u : 0u);
+  __threadfence();  // the partial row is visible device-wide before the counter moves
+  uint32_t old = 0;
+  if (lane == 0) old = atomicAdd(&counters[first_slot], 1u);
+  old = __builtin_amdgcn_readfirstlane(old);
+  if (old != m1 - m0) return;
+  __threadfence();  // last window of the cluster: every other partial row is complete and visible
+  const uint32_t nwin = m1 - m0 + 1;
+  const float fn = (float)(hi - lo);
+  char* dst = centroids + (size_t)s * row_bytes;
+  constexpr int kRows = 8;
+  for (uint32_t c = lane; c < cpr; c += 64) {
+    float acc[E], comp[E];
 #pragma unroll
-      for (int i = 0; i < E; ++i) comp[i] = 0.0f;
-      for (; p < hi; p += 4) {
-        uint4 q[4];
+    for (int i = 0; i < E; ++i) acc[i] = comp[i] = 0.0f;
+    for (uint32_t j = 0; j < nwin; j += kRows) {
+      float x[kRows][E];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (p + u < hi) q[u] = load16(tokens + (size_t)((uint32_t)uniform<LPR>(perm[p + u]) / k) * row_bytes + c * 16);
+      for (int u = 0; u < kRows; ++u) {
+        const uint32_t jj = min(j + u, nwin - 1);
+        const float* src = partial + (size_t)(jj == 0 ? first_slot : 2 * (m0 + jj)) * d + (size_t)c * E;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (p + u >= hi) break;
-          Piece<DT>::widen(q[u], x);
+        for (int i = 0; i < E; i += 4) {
+          const float4 v = *(const float4*)(src + i);
+          x[u][i] = v.x; x[u][i + 1] = v.y; x[u][i + 2] = v.z; x[u][i + 3] = v.w;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kRows; ++u) {
+        if (j + u < nwin) {
 #pragma unroll
           for (int i = 0; i < E; ++i) {
-            const float y = x[i] - comp[i];
+            const float y = x[u][i] - comp[i];
             const float t = acc[i] + y;
             comp[i] = (t - acc[i]) - y;
             acc[i] = t;
@@ -87,7 +136,6 @@ __global__ __launch_bounds__(256) void centroid_kernel(
         }
       }
     }
-    const float fn = (float)n;
 #pragma unroll
     for (int i = 0; i < E; ++i) acc[i] /= fn;
     store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
@@ -95,31 +143,140 @@ __global__ __launch_bounds__(256) void centroid_kernel(
 }
 
 template <typename DT, int LPR>
-void launch_lpr(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* num_segments,
-                void* centroids, int64_t N, int k, uint32_t cpr, hipStream_t stream) {
+__global__ __launch_bounds__(256) void centroid_kernel(
+    const char* __restrict__ tokens, const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_offsets,
+    const int32_t* __restrict__ seg_of, const int32_t* __restrict__ num_segments, char* __restrict__ centroids,
+    float* partial, uint32_t* counters, uint32_t N, uint32_t k, uint32_t cpr) {
+  constexpr int G = 64 / LPR;  // clusters handled side by side by one wave
+  constexpr int E = Piece<DT>::kElems;
+  const uint32_t S = (uint32_t)*num_segments;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t wave = (blockIdx.x * 256u + threadIdx.x) >> 6;
+  const uint32_t s = wave * G + lane / LPR;
+  const size_t row_bytes = (size_t)cpr * 16;
+  if (s < S) {
+    const int32_t lo = uniform<LPR>(seg_offsets[s]), hi = uniform<LPR>(seg_offsets[s + 1]);
+    const int32_t n = hi - lo;
+    if (n <= kCentroidWindow) {
+      const char* first = tokens + (size_t)((uint32_t)uniform<LPR>(perm[lo]) / k) * row_bytes;
+      char* dst = centroids + (size_t)s * row_bytes;
+      for (uint32_t c = lane % LPR; c < cpr; c += LPR) {
+        const uint4 v0 = load16(first + c * 16);
+        if (n == 1) {  // the mean of one row is the row
+          store16_stream(dst + c * 16, v0);
+          continue;
+        }
+        float acc[E], x[E];
+        Piece<DT>::widen(v0, acc);
+        int32_t p = lo + 1;
+        if (n <= kPlainSumMax) {
+          for (; p + 4 <= hi; p += 4) {
+            uint4 q[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              q[u] = load16(tokens + (size_t)((uint32_t)uniform<LPR>(perm[p + u]) / k) * row_bytes + c * 16);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              Piece<DT>::widen(q[u], x);
+#pragma unroll
+              for (int i = 0; i < E; ++i) acc[i] += x[i];
+            }
+          }
+          for (; p < hi; ++p) {
+            Piece<DT>::widen(load16(tokens + (size_t)((uint32_t)uniform<LPR>(perm[p]) / k) * row_bytes + c * 16), x);
+#pragma unroll
+            for (int i = 0; i < E; ++i) acc[i] += x[i];
+          }
+        } else {
+          // longer cluster: compensated (Kahan) summation keeps the binary32 sum within
+          // a couple of ulps of the exact one however many members there are
+          float comp[E];
+#pragma unroll
+          for (int i = 0; i < E; ++i) comp[i] = 0.0f;
+          for (; p < hi; p += 4) {
+            uint4 q[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              if (p + u < hi)
+                q[u] = load16(tokens + (size_t)((uint32_t)uniform<LPR>(perm[p + u]) / k) * row_bytes + c * 16);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              if (p + u >= hi) break;
+              Piece<DT>::widen(q[u], x);
+#pragma unroll
+              for (int i = 0; i < E; ++i) {
+                const float y = x[i] - comp[i];
+                const float t = acc[i] + y;
+                comp[i] = (t - acc[i]) - y;
+                acc[i] = t;
+              }
+            }
+          }
+        }
+        const float fn = (float)n;
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] /= fn;
+        store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
+      }
+    }
+  }
+  // window duty: wave m looks after block m of the sorted positions
+  if ((uint64_t)wave * kCentroidWindow >= N) return;
+  const uint32_t p0 = wave * (uint32_t)kCentroidWindow;
+  const uint32_t p1 = min(p0 + (uint32_t)kCentroidWindow, N);
+  const uint32_t d = cpr * E;
+  const int32_t sf = __builtin_amdgcn_readfirstlane(seg_of[perm[p0]]);
+  const int32_t sl = __builtin_amdgcn_readfirstlane(seg_of[perm[p1 - 1]]);
+  {
+    const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[sf]);
+    const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[sf + 1]);
+    if (hi - lo > kCentroidWindow)
+      long_cluster_window<DT>(tokens, perm, seg_offsets, centroids, partial, counters, sf, (int32_t)p0,
+                              min(hi, (int32_t)p1), 2 * wave, k, cpr, d);
+  }
+  if (sl != sf) {
+    const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[sl]);
+    const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[sl + 1]);
+    if (hi - lo > kCentroidWindow)
+      long_cluster_window<DT>(tokens, perm, seg_offsets, centroids, partial, counters, sl, lo, (int32_t)p1,
+                              2 * wave + 1, k, cpr, d);
+  }
+}
+
+template <typename DT, int LPR>
+void launch_lpr(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
+                const int32_t* num_segments, void* centroids, float* partial, uint32_t* counters, int64_t N, int k,
+                uint32_t cpr, hipStream_t stream) {
   constexpr int G = 64 / LPR;
   const uint64_t waves = ((uint64_t)N + G - 1) / G;  // worst case S == N; surplus waves leave at once
   const uint32_t blocks = (uint32_t)((waves + 3) / 4);
   hipLaunchKernelGGL((centroid_kernel<DT, LPR>), dim3(blocks), dim3(256), 0, stream, (const char*)tokens, perm,
-                     seg_offsets, num_segments, (char*)centroids, (uint32_t)k, cpr);
+                     seg_offsets, seg_of, num_segments, (char*)centroids, partial, counters, (uint32_t)N, (uint32_t)k,
+                     cpr);
 }
 
 template <typename DT>
-void launch_typed(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* num_segments,
-                  void* centroids, int64_t N, int k, uint32_t cpr, hipStream_t stream) {
-  if (cpr > 16) launch_lpr<DT, 64>(tokens, perm, seg_offsets, num_segments, centroids, N, k, cpr, stream);
-  else if (cpr > 4) launch_lpr<DT, 16>(tokens, perm, seg_offsets, num_segments, centroids, N, k, cpr, stream);
-  else launch_lpr<DT, 4>(tokens, perm, seg_offsets, num_segments, centroids, N, k, cpr, stream);
+void launch_typed(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
+                  const int32_t* num_segments, void* centroids, float* partial, uint32_t* counters, int64_t N, int k,
+                  uint32_t cpr, hipStream_t stream) {
+  if (cpr > 16)
+    launch_lpr<DT, 64>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
+  else if (cpr > 4)
+    launch_lpr<DT, 16>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
+  else
+    launch_lpr<DT, 4>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
 }
 
 }  // namespace
 
-hipError_t launch_centroid(const void* tokens, const int32_t* perm, const int32_t* seg_offsets,
-                           const int32_t* num_segments, void* centroids, int64_t N, int k, int d, bool bf16,
-                           hipStream_t stream) {
+hipError_t launch_centroid(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
+                           const int32_t* num_segments, void* centroids, float* partial, uint32_t* counters, int64_t N,
+                           int k, int d, bool bf16, hipStream_t stream) {
   const uint32_t cpr = (uint32_t)((size_t)d * (bf16 ? 2 : 4) / 16);
-  if (bf16) launch_typed<BF16>(tokens, perm, seg_offsets, num_segments, centroids, N, k, cpr, stream);
-  else launch_typed<F32>(tokens, perm, seg_offsets, num_segments, centroids, N, k, cpr, stream);
+  if (bf16)
+    launch_typed<BF16>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
+  else
+    launch_typed<F32>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
   return hipGetLastError();
 }
 

@@ -297,9 +297,14 @@ __device__ __forceinline__ void load_heads(const uint64_t* __restrict__ key, uin
   }
 }
 
+// Also clears the centroid step's window counters (each tile clears those of its own positions).
 __global__ __launch_bounds__(kSegThreads) void seg_count_kernel(const uint64_t* __restrict__ key, uint32_t N,
-                                                                uint32_t nblk, uint32_t* __restrict__ blocksum) {
+                                                                uint32_t nblk, uint32_t* __restrict__ blocksum,
+                                                                uint32_t* __restrict__ window_counters) {
   __shared__ uint32_t wave_sum[kSegThreads / kWave];
+  constexpr uint32_t kCountersPerTile = 2 * kSegTile / kCentroidWindow;
+  static_assert(kSegTile % kCentroidWindow == 0 && kCountersPerTile <= kSegThreads, "window counters per tile");
+  if (threadIdx.x < kCountersPerTile) window_counters[blockIdx.x * kCountersPerTile + threadIdx.x] = 0;
   const uint32_t base = blockIdx.x * kSegTile + threadIdx.x * kSegItems;
   uint64_t kv[kSegItems + 1];
   bool head[kSegItems];
@@ -380,6 +385,7 @@ struct SmallArgs {
   uint64_t* keybuf[2];
   int32_t* idxbuf[2];
   int32_t *seg_offsets, *seg_expert, *expert_offsets, *perm, *seg_of, *num_segments;
+  uint32_t* window_counters;  // cleared here for the centroid step
 };
 
 constexpr int kSmallWaves = 16;
@@ -411,6 +417,7 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_group_kernel(KeySource
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   const uint32_t N = a.N;
+  if (threadIdx.x < 2 * ((N + kCentroidWindow - 1) / kCentroidWindow)) a.window_counters[threadIdx.x] = 0;
   const uint32_t slice = ((N + kSmallWaves - 1) / kSmallWaves + 63u) & ~63u;  // keys per wave, whole rounds
   const uint32_t lo = min((uint32_t)wave * slice, N), hi = min(lo + slice, N);
 
@@ -557,7 +564,7 @@ hipError_t launch_scatter(const KeySource& src, uint32_t N, const PassArgs& a, u
 
 }  // namespace
 
-bool plan_group(int64_t T, int k, int E, int L, int r, GroupPlan* plan) {
+bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
   uint64_t nb = 1;  // (2r)^L, known to be < 2^63 by the caller's check
   for (int l = 0; l < L; ++l) nb *= (uint64_t)(2 * r);
   GroupPlan p{};
@@ -590,6 +597,12 @@ bool plan_group(int64_t T, int k, int E, int L, int r, GroupPlan* plan) {
   off = align256(off + (size_t)kGroupBins * p.sort_blocks * 4);
   p.off_blocksum = off;
   off = align256(off + ((size_t)p.seg_blocks + 1) * 4);
+  const size_t windows = 2 * (size_t)((p.N + kCentroidWindow - 1) / kCentroidWindow);
+  p.off_partial = off;
+  off = align256(off + windows * (size_t)d * 4);
+  p.off_counters = off;
+  // every numbering tile clears the counters of its whole tile, so the count is rounded up to whole tiles
+  off = align256(off + (size_t)p.seg_blocks * (2 * kSegTile / kCentroidWindow) * 4);
   p.total_bytes = off;
   *plan = p;
   return true;
@@ -621,6 +634,7 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     a.idxbuf[0] = idxbuf[0]; a.idxbuf[1] = idxbuf[1];
     a.seg_offsets = seg_offsets; a.seg_expert = seg_expert; a.expert_offsets = expert_offsets;
     a.perm = perm; a.seg_of = seg_of; a.num_segments = num_segments;
+    a.window_counters = (uint32_t*)(ws + plan.off_counters);
     hipLaunchKernelGGL(small_group_kernel, dim3(1), dim3(kSmallWaves * 64), 0, stream, src, a);
     return hipGetLastError();
   }
@@ -658,7 +672,8 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     sorted_key = dkey;
   }
   const uint32_t sblk = plan.seg_blocks;
-  hipLaunchKernelGGL(seg_count_kernel, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, N, sblk, blocksum);
+  hipLaunchKernelGGL(seg_count_kernel, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, N, sblk, blocksum,
+                     (uint32_t*)(ws + plan.off_counters));
   if (sblk <= (uint32_t)kSelfPrefixMaxTiles) {
     hipLaunchKernelGGL(seg_write_kernel<true>, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, perm, N,
                        (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert, expert_offsets, seg_of,

@@ -31,20 +31,26 @@ struct GroupPlan {
   uint32_t sort_blocks;  // tiles of kSortTile assignments
   uint32_t seg_blocks;   // tiles of kSegTile sorted positions
   // byte offsets into the workspace
-  size_t off_key[2], off_idx[2], off_table, off_blocksum, total_bytes;
+  size_t off_key[2], off_idx[2], off_table, off_blocksum;
+  size_t off_partial, off_counters;  // window sums and window counters of the centroid step
+  size_t total_bytes;
 };
 
-// Fills the plan; returns false when ebits + bbits > 64.
-bool plan_group(int64_t T, int k, int E, int L, int r, GroupPlan* plan);
+constexpr int kCentroidWindow = 128;  // clusters with more members are summed in windows of this many positions
+
+// Fills the plan (d = elements per token row); returns false when ebits + bbits > 64.
+bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan);
 
 hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint64_t* bucket, int k, int E,
                         int32_t* seg_offsets, int32_t* seg_expert, int32_t* expert_offsets, int32_t* perm,
                         int32_t* seg_of, int32_t* num_segments, char* workspace, hipStream_t stream);
 
 // ---- step 3: centroid ---------------------------------------------------
-hipError_t launch_centroid(const void* tokens, const int32_t* perm, const int32_t* seg_offsets,
-                           const int32_t* num_segments, void* centroids, int64_t N, int k, int d, bool bf16,
-                           hipStream_t stream);
+// partial: 2 * ceil(N / kCentroidWindow) rows of d binary32 sums; counters: as many counts, zero on entry
+// (launch_group clears them).
+hipError_t launch_centroid(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
+                           const int32_t* num_segments, void* centroids, float* partial, uint32_t* counters, int64_t N,
+                           int k, int d, bool bf16, hipStream_t stream);
 
 // ---- step 4: restore ----------------------------------------------------
 hipError_t launch_restore(const void* tokens, const void* centroids, const void* expert_out,

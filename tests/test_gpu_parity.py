@@ -108,6 +108,45 @@ def test_all_tokens_identical_one_cluster(H, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,k", [(64, 1), (1032, 1), (520, 2)])
+def test_long_clusters_are_summed_in_windows(H, dtype, d, k):
+    # cluster sizes around the window length of the centroid step (128 sorted positions) and far beyond it, with
+    # heads on and off the window grid; d = 1032 makes rows wider than one pass of a wave over the row
+    sizes = [128, 129, 1, 127, 256, 257, 3, 1000, 2, 5000, 131, 1, 1, 384, 640, 7, 2049]
+    T, E, L, r = sum(sizes), 3, 2, 16
+    tokens, rot, _ = _rand_inputs(21, T, d, 1, E, L, r, dtype)
+    rng = np.random.default_rng(22)
+    group = np.repeat(np.arange(len(sizes)), sizes)
+    where = rng.permutation(T)                       # members of a cluster are scattered over the tokens
+    ids = np.empty(T, np.uint64)
+    ids[where] = group.astype(np.uint64)
+    if k == 1:
+        expert = np.empty((T, 1), np.int32)
+        expert[where, 0] = group * E // len(sizes)   # non-decreasing with the group: cluster order = group order
+    else:
+        expert = np.tile(np.array([[2, 0]], np.int32), (T, 1))
+    run = H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn, bucket_override=ids)
+    assert run.S == k * len(sizes)
+    n = np.diff(run.out.seg_offsets[:run.S + 1].cpu().numpy())
+    assert sorted(n.tolist()) == sorted(sizes * k)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_one_huge_cluster_many_windows(H, dtype):
+    # 20000 identical tokens on the multi-launch grouping route: 157 window sums are combined by the last wave
+    T, d, E = 20000, 64, 2
+    tokens, rot, _ = _rand_inputs(23, 1, d, 1, E, 2, 16, dtype)
+    tokens = np.repeat(tokens, T, axis=0)
+    expert = np.ones((T, 1), np.int32)
+    run = H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn)
+    assert run.S == 1
+    if dtype == "bf16":
+        assert np.array_equal(run.centroids[0], tokens[0])
+    else:
+        assert np.all(np.abs(run.centroids[0] - tokens[0]) <= 2.0 ** -23 * np.abs(tokens[0]))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_every_token_its_own_cluster_reconstructs_exactly(H, dtype):
     # supplied bucket ids are all distinct: every cluster has one member, Y == E(x) bit for bit
     T, d, k, E, L, r = 1111, 48, 2, 4, 4, 64
