@@ -11,15 +11,18 @@ used as steps: numpy matmul (the rotation), numpy lexsort (the stable sort),
 numpy add.reduceat (the per-bucket sums).
 
 Storage convention for arrays: "f32" = numpy float32, "bf16" = numpy uint16
-holding the upper half of the binary32 pattern.
+holding the upper half of the binary32 pattern, "f64" = numpy float64 (no
+rounding at all; used by the finite-difference pins of the backward pass).
 
 Pins (tests/test_oracle_*.py): pure-Python brute force on tiny inputs, the
 cross-polytope invariants (positive scaling, negation, row permutation of R),
 identity / orthonormal closed forms, dict- and numpy.unique-based grouping,
 mass conservation, exact reconstruction for singleton buckets, the linear
-expert closed form.  Absolute values of the whole path on the synthetic
-workloads have no printed counterpart in the paper: beyond those pins they
-are parity unpinned.
+expert closed form; for the backward pass central finite differences of the
+forward functions of this file, its closed forms for one-member clusters and
+for an identity expert, and gradient mass conservation.  Absolute values of
+the whole path on the synthetic workloads have no printed counterpart in the
+paper: beyond those pins they are parity unpinned.
 """
 from __future__ import annotations
 
@@ -31,6 +34,9 @@ import numpy as np
 # --------------------------------------------------------------------------
 def widen(x: np.ndarray, dtype: str) -> np.ndarray:
     """Exact conversion of a storage array to float64."""
+    if dtype == "f64":
+        assert x.dtype == np.float64
+        return x
     if dtype == "f32":
         assert x.dtype == np.float32
         return x.astype(np.float64)
@@ -44,7 +50,10 @@ def widen(x: np.ndarray, dtype: str) -> np.ndarray:
 def narrow(x64: np.ndarray, dtype: str) -> np.ndarray:
     """Round float64 to the storage type: binary64 -> binary32 with
     round-to-nearest-even, then (bf16 only) binary32 -> bfloat16 with
-    round-to-nearest-even on the discarded 16 bits.  Finite inputs only."""
+    round-to-nearest-even on the discarded 16 bits.  Finite inputs only.
+    "f64" keeps the values as they are."""
+    if dtype == "f64":
+        return np.asarray(x64, dtype=np.float64)
     f32 = np.asarray(x64, dtype=np.float64).astype(np.float32)
     if dtype == "f32":
         return f32
@@ -194,6 +203,50 @@ def restore_ref(tokens: np.ndarray, centroids: np.ndarray, expert_out: np.ndarra
         w = gate_weight.astype(np.float64).reshape(T, k, 1)
         y = (w * y.reshape(T, k, -1)).sum(axis=1)
     return narrow(y, dtype)
+
+
+# --------------------------------------------------------------------------
+# Backward of steps 3 and 4.  The paper does not describe it (it counts the
+# backward all-to-alls in Section 3.1 but says nothing of how gradients pass
+# through the compression); this is the chain rule applied to
+#     c_s = (1/n_s) sum_{a in s} x_a,   Y_a = EC_s + (x_a - c_s)
+# with the cluster membership held fixed.
+# --------------------------------------------------------------------------
+def restore_backward_ref(grad_out: np.ndarray, perm: np.ndarray, seg_offsets: np.ndarray, dtype: str):
+    """Gradient with respect to the expert outputs: EC_s reaches every member
+    row unchanged, so dL/dEC_s = sum_{a in s} grad_out[a].  grad_out is
+    [N, d] in assignment order; the result is [S, d], rounded once."""
+    S = seg_offsets.size - 1
+    g = widen(grad_out, dtype)
+    rows = g[perm.astype(np.int64)]                # [N, d] in sorted order
+    sums = np.add.reduceat(rows, seg_offsets[:-1].astype(np.int64), axis=0) if S > 0 \
+        else np.zeros((0, g.shape[1]))
+    return narrow(sums, dtype)
+
+
+def compress_backward_ref(grad_out: np.ndarray, grad_centroids: np.ndarray, grad_expert_out: np.ndarray,
+                          seg_of: np.ndarray, seg_offsets: np.ndarray, k: int, dtype: str,
+                          no_residual: bool = False):
+    """Gradient with respect to the tokens.  grad_centroids[s] is what the
+    expert's backward returns for its input c_s; grad_expert_out[s] is the
+    stored result of restore_backward_ref.  The centroid enters Y_a of every
+    member with coefficient -1, so the total gradient of c_s is
+    grad_centroids[s] - grad_expert_out[s], and c_s depends on each member
+    with weight 1/n_s:
+        dL/dx_t = sum_j ( grad_out[a] + (grad_centroids[s] - grad_expert_out[s]) / n_s ),
+        a = t*k + j, s = seg_of[a].
+    Without the residual term (no_residual) Y_a = EC_s and only
+    grad_centroids[s] / n_s remains.  Result [T, d], rounded once."""
+    s = seg_of.astype(np.int64)
+    N = s.size
+    T = N // k
+    n = np.diff(seg_offsets.astype(np.int64)).astype(np.float64)[s][:, None]
+    h = widen(grad_centroids, dtype)[s]
+    if no_residual:
+        per_a = h / n
+    else:
+        per_a = widen(grad_out, dtype) + (h - widen(grad_expert_out, dtype)[s]) / n
+    return narrow(per_a.reshape(T, k, -1).sum(axis=1), dtype)
 
 
 # --------------------------------------------------------------------------
