@@ -9,6 +9,8 @@
  *                      replace every cluster by its centroid        (Alg. 1, the two nested loops)
  *   lshmoe_decompress  give every token the expert output of its
  *                      centroid plus the token's residual           (Eq. 4, Eq. 5)
+ *   lshmoe_decompress_combine   the same fused with the gate-weighted sum over a token's experts (Eq. 2)
+ *   lshmoe_decompress_backward, lshmoe_compress_backward   gradients through the two calls above
  *
  * Notation: T tokens of dimension d; every token is routed to k distinct
  * experts out of E (assignment a = t*k + j is token t's j-th expert, N = T*k
@@ -197,6 +199,74 @@ lshmoe_status lshmoe_decompress_combine(const void* tokens, const void* centroid
                                         const float* gate_weight,
                                         int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, uint32_t flags,
                                         void* out, void* stream);
+
+/*
+ * Backward of lshmoe_decompress / lshmoe_compress with the cluster membership
+ * held fixed.  The paper gives no formula for it (Section 3.1 only counts the
+ * backward all-to-alls); these two calls are the chain rule applied to the
+ * centroid formula of Section 2.3 and to Eq. 4 / Eq. 5:
+ *     c_s = (1/n_s) * sum_{a in s} x_a,      Y_a = EC_s + (x_a - c_s).
+ * Order of use: lshmoe_decompress_backward turns dL/dY into dL/dEC (S rows, the
+ * payload of the backward all-to-all); the experts' backward returns dL/dc for
+ * their inputs; lshmoe_compress_backward turns both into dL/dx.
+ */
+
+/* Bytes of device scratch lshmoe_decompress_backward needs (host only).  A
+ * workspace sized by lshmoe_workspace_bytes for the same T, d, k is also
+ * large enough.  Errors: as for lshmoe_workspace_bytes. */
+lshmoe_status lshmoe_backward_workspace_bytes(int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype,
+                                              size_t* out_bytes);
+
+/*
+ * Gradient with respect to the expert outputs: EC_s reaches every member row of
+ * cluster s unchanged (Eq. 5), so
+ *     grad_expert_out[s, :] = sum_{a in s} grad_out[a, :],
+ * members in perm order, accumulated in binary32 (compensated beyond 16
+ * members) and rounded once; reproducible bit for bit.
+ *
+ *   grad_out        [T, k, d] in   dtype; dL/dY in assignment order
+ *   perm, seg_offsets, seg_of, num_segments   in, as written by lshmoe_compress
+ *   grad_expert_out [N, d]    out  dtype; rows 0..S-1 are written
+ *   workspace                 scratch of at least lshmoe_backward_workspace_bytes(...) bytes, 256-byte
+ *                             aligned; contents on entry are ignored
+ *
+ * Errors: NULL pointer; T, d, k <= 0; N >= 2^30 (UNSUPPORTED); row size not a
+ * multiple of 16 bytes (UNSUPPORTED); workspace too small or misaligned
+ * (WORKSPACE); launch failure (HIP).
+ */
+lshmoe_status lshmoe_decompress_backward(const void* grad_out, const int32_t* perm, const int32_t* seg_offsets,
+                                         const int32_t* seg_of, const int32_t* num_segments,
+                                         int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype,
+                                         void* grad_expert_out, void* workspace, size_t workspace_bytes,
+                                         void* stream);
+
+/*
+ * Gradient with respect to the tokens.  The centroid c_s enters the expert
+ * (gradient grad_centroids[s]) and, with coefficient -1, every member's Y_a
+ * (gradient -grad_expert_out[s] in total), and depends on each member with
+ * weight 1/n_s:
+ *     grad_tokens[t, :] = sum_{j<k} ( grad_out[a, :] + (grad_centroids[s, :] - grad_expert_out[s, :]) / n_s ),
+ *     a = t*k + j,  s = seg_of[a],  n_s = seg_offsets[s+1] - seg_offsets[s],
+ * in binary32 in the order j = 0..k-1, rounded once.  For a one-member cluster
+ * the term is grad_centroids[s, :] (grad_expert_out[s] is then the row
+ * grad_out[a] itself).  With LSHMOE_FLAG_NO_RESIDUAL (forward Y_a = EC_s) the
+ * term is grad_centroids[s, :] / n_s, and grad_out and grad_expert_out may be
+ * NULL.
+ *
+ *   grad_out        [T, k, d] in   dtype
+ *   grad_centroids  [S, d]    in   dtype; the experts' gradient for their inputs, cluster order
+ *   grad_expert_out [S, d]    in   dtype; as written by lshmoe_decompress_backward
+ *   seg_of [N], seg_offsets [S+1]  in, as written by lshmoe_compress
+ *   grad_tokens     [T, d]    out  dtype
+ *
+ * Errors: NULL pointer; T, d, k <= 0; N >= 2^30 (UNSUPPORTED); unknown flag
+ * bits (UNSUPPORTED); row size not a multiple of 16 bytes (UNSUPPORTED); launch
+ * failure (HIP).
+ */
+lshmoe_status lshmoe_compress_backward(const void* grad_out, const void* grad_centroids, const void* grad_expert_out,
+                                       const int32_t* seg_of, const int32_t* seg_offsets,
+                                       int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, uint32_t flags,
+                                       void* grad_tokens, void* stream);
 
 #ifdef __cplusplus
 }

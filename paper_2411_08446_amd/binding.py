@@ -61,6 +61,12 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.lshmoe_decompress.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
     lib.lshmoe_decompress_combine.restype = ctypes.c_int
     lib.lshmoe_decompress_combine.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
+    lib.lshmoe_backward_workspace_bytes.restype = ctypes.c_int
+    lib.lshmoe_backward_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.lshmoe_decompress_backward.restype = ctypes.c_int
+    lib.lshmoe_decompress_backward.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
+    lib.lshmoe_compress_backward.restype = ctypes.c_int
+    lib.lshmoe_compress_backward.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
     _lib = lib
     return lib
 
@@ -189,3 +195,40 @@ def lshmoe_decompress_combine(tokens: torch.Tensor, centroids: torch.Tensor, exp
         _ptr(tokens), _ptr(centroids), _ptr(expert_out), _ptr(seg_of, torch.int32),
         _ptr(seg_offsets, torch.int32), _ptr(gate_weight, torch.float32), T, d, k, _dtype_code(tokens), flags,
         _ptr(out), _stream(stream)))
+
+
+def lshmoe_backward_workspace_bytes(T: int, d: int, k: int, dtype_code: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().lshmoe_backward_workspace_bytes(T, d, k, dtype_code, ctypes.byref(out)))
+    return int(out.value)
+
+
+def lshmoe_decompress_backward(grad_out: torch.Tensor, perm: torch.Tensor, seg_offsets: torch.Tensor,
+                               seg_of: torch.Tensor, num_segments: torch.Tensor, grad_expert_out: torch.Tensor,
+                               workspace: torch.Tensor, stream=None) -> None:
+    """grad_out [T, k, d] -> grad_expert_out [N, d] (rows 0..S-1): per-cluster sums of the output gradient."""
+    T, k, d = grad_out.shape
+    N = T * k
+    if perm.numel() != N or seg_of.numel() != N or seg_offsets.numel() < 2 or grad_expert_out.shape != (N, d) \
+            or grad_expert_out.dtype != grad_out.dtype:
+        raise ValueError("perm and seg_of must have N entries and grad_expert_out be [N, d] of the gradient dtype")
+    ws_ptr, ws_bytes = _aligned_ws(workspace)
+    i32 = torch.int32
+    _check(load_library().lshmoe_decompress_backward(
+        _ptr(grad_out), _ptr(perm, i32), _ptr(seg_offsets, i32), _ptr(seg_of, i32), _ptr(num_segments, i32),
+        T, d, k, _dtype_code(grad_out), _ptr(grad_expert_out), ws_ptr, ws_bytes, _stream(stream)))
+
+
+def lshmoe_compress_backward(grad_out, grad_centroids: torch.Tensor, grad_expert_out, seg_of: torch.Tensor,
+                             seg_offsets: torch.Tensor, k: int, grad_tokens: torch.Tensor, flags: int = 0,
+                             stream=None) -> None:
+    """grad_tokens [T, d] = sum_j grad_out[a] + (grad_centroids[s] - grad_expert_out[s]) / n_s."""
+    T, d = grad_tokens.shape
+    if seg_of.numel() != T * k or grad_centroids.dtype != grad_tokens.dtype:
+        raise ValueError("seg_of must have T*k entries and the gradients the dtype of grad_tokens")
+    for g in (grad_out, grad_expert_out):
+        if g is not None and g.dtype != grad_tokens.dtype:
+            raise TypeError("gradients must share one dtype")
+    _check(load_library().lshmoe_compress_backward(
+        _ptr(grad_out), _ptr(grad_centroids), _ptr(grad_expert_out), _ptr(seg_of, torch.int32),
+        _ptr(seg_offsets, torch.int32), T, d, k, _dtype_code(grad_tokens), flags, _ptr(grad_tokens), _stream(stream)))

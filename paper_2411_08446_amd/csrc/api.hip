@@ -73,6 +73,18 @@ lshmoe_status check_compress_shape(int64_t T, int d, int k, int E, int L, int r,
   return LSHMOE_OK;
 }
 
+// T, d, k and the row size of an entry point that moves [N, d] rows.
+lshmoe_status check_rows_shape(int64_t T, int d, int k, int dt) {
+  if (T <= 0 || d <= 0 || k <= 0)
+    return fail(LSHMOE_ERR_SHAPE, "T, d, k must be positive (T=%lld, d=%d, k=%d)", (long long)T, d, k);
+  if (lshmoe_status st = check_row(d, dt)) return st;
+  if (T >= kMaxAssignments || T * (int64_t)k >= kMaxAssignments)
+    return fail(LSHMOE_ERR_UNSUPPORTED, "N = T*k = %lld assignments; the limit is 2^30 - 1", (long long)(T * (int64_t)k));
+  if ((uint64_t)T * (uint64_t)k * ((size_t)d * item_size(dt) / 16) > 0xffffff00ull)
+    return fail(LSHMOE_ERR_UNSUPPORTED, "N*d is too large for one launch");
+  return LSHMOE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -91,7 +103,7 @@ const char* lshmoe_status_string(int status) {
 
 const char* lshmoe_last_error(void) { return g_err; }
 
-int lshmoe_abi_version(void) { return 2; }
+int lshmoe_abi_version(void) { return 3; }
 
 lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E, int32_t L, int32_t r,
                                      lshmoe_dtype dtype, size_t* out_bytes) {
@@ -135,7 +147,8 @@ lshmoe_status lshmoe_compress(const void* tokens, const int32_t* expert, const u
   if (e != hipSuccess) return hip_fail("group launch", e);
   e = lshmoe::launch_centroid(tokens, perm, seg_offsets, seg_of, num_segments, centroids,
                               (float*)((char*)workspace + plan.off_partial),
-                              (uint32_t*)((char*)workspace + plan.off_counters), plan.N, k, d, dtype == LSHMOE_BF16, s);
+                              (uint32_t*)((char*)workspace + plan.off_counters), plan.N, k, d, dtype == LSHMOE_BF16,
+                              /*mean=*/true, s);
   if (e != hipSuccess) return hip_fail("centroid launch", e);
   return ok();
 }
@@ -174,6 +187,53 @@ lshmoe_status lshmoe_decompress_combine(const void* tokens, const void* centroid
   hipError_t e = lshmoe::launch_restore_combine(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, out, T,
                                                 k, d, dtype == LSHMOE_BF16, flags, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("restore-combine launch", e);
+  return ok();
+}
+
+lshmoe_status lshmoe_backward_workspace_bytes(int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, size_t* out_bytes) {
+  if (!out_bytes) return fail(LSHMOE_ERR_NULL, "out_bytes is NULL");
+  if (lshmoe_status st = check_rows_shape(T, d, k, (int)dtype)) return st;
+  *out_bytes = lshmoe::plan_backward(T * (int64_t)k, d).total_bytes;
+  return ok();
+}
+
+lshmoe_status lshmoe_decompress_backward(const void* grad_out, const int32_t* perm, const int32_t* seg_offsets,
+                                         const int32_t* seg_of, const int32_t* num_segments, int64_t T, int32_t d,
+                                         int32_t k, lshmoe_dtype dtype, void* grad_expert_out, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+  if (!grad_out || !perm || !seg_offsets || !seg_of || !num_segments || !grad_expert_out)
+    return fail(LSHMOE_ERR_NULL, "an input or output pointer is NULL");
+  if (lshmoe_status st = check_rows_shape(T, d, k, (int)dtype)) return st;
+  const int64_t N = T * (int64_t)k;
+  const lshmoe::BackwardPlan plan = lshmoe::plan_backward(N, d);
+  if (!workspace) return fail(LSHMOE_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", plan.total_bytes);
+  if (((uintptr_t)workspace & 255u) != 0) return fail(LSHMOE_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < plan.total_bytes)
+    return fail(LSHMOE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.total_bytes);
+  hipStream_t s = (hipStream_t)stream;
+  uint32_t* counters = (uint32_t*)((char*)workspace + plan.off_counters);
+  hipError_t e = lshmoe::launch_clear_counters(counters, plan.windows, s);
+  if (e != hipSuccess) return hip_fail("counter clear launch", e);
+  // a segment sum over the rows of grad_out: row of sorted position p is grad_out[perm[p]]
+  e = lshmoe::launch_centroid(grad_out, perm, seg_offsets, seg_of, num_segments, grad_expert_out,
+                              (float*)((char*)workspace + plan.off_partial), counters, N, /*k=*/1, d,
+                              dtype == LSHMOE_BF16, /*mean=*/false, s);
+  if (e != hipSuccess) return hip_fail("segment sum launch", e);
+  return ok();
+}
+
+lshmoe_status lshmoe_compress_backward(const void* grad_out, const void* grad_centroids, const void* grad_expert_out,
+                                       const int32_t* seg_of, const int32_t* seg_offsets, int64_t T, int32_t d,
+                                       int32_t k, lshmoe_dtype dtype, uint32_t flags, void* grad_tokens, void* stream) {
+  if (!grad_centroids || !seg_of || !seg_offsets || !grad_tokens)
+    return fail(LSHMOE_ERR_NULL, "an input or output pointer is NULL");
+  if (flags & ~(uint32_t)LSHMOE_FLAG_NO_RESIDUAL) return fail(LSHMOE_ERR_UNSUPPORTED, "unknown flag bits 0x%x", flags);
+  if (!(flags & LSHMOE_FLAG_NO_RESIDUAL) && (!grad_out || !grad_expert_out))
+    return fail(LSHMOE_ERR_NULL, "grad_out and grad_expert_out are required unless LSHMOE_FLAG_NO_RESIDUAL is set");
+  if (lshmoe_status st = check_rows_shape(T, d, k, (int)dtype)) return st;
+  hipError_t e = lshmoe::launch_grad_tokens(grad_out, grad_centroids, grad_expert_out, seg_of, seg_offsets, grad_tokens,
+                                            T, k, d, dtype == LSHMOE_BF16, flags, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("token gradient launch", e);
   return ok();
 }
 

@@ -88,7 +88,7 @@ template <typename DT>
 __device__ __forceinline__ void long_cluster_window(
     const char* __restrict__ tokens, const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_offsets,
     char* __restrict__ centroids, float* partial, uint32_t* counters, int32_t s, int32_t a, int32_t b, uint32_t slot,
-    uint32_t k, uint32_t cpr, uint32_t d) {
+    uint32_t k, uint32_t cpr, uint32_t d, uint32_t mean) {
   constexpr int E = Piece<DT>::kElems;
   const size_t row_bytes = (size_t)cpr * 16;
   const uint32_t lane = threadIdx.x & 63;
@@ -136,8 +136,10 @@ __device__ __forceinline__ void long_cluster_window(
         }
       }
     }
+    if (mean) {
 #pragma unroll
-    for (int i = 0; i < E; ++i) acc[i] /= fn;
+      for (int i = 0; i < E; ++i) acc[i] /= fn;
+    }
     store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
   }
 }
@@ -146,7 +148,7 @@ template <typename DT, int LPR>
 __global__ __launch_bounds__(256) void centroid_kernel(
     const char* __restrict__ tokens, const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_offsets,
     const int32_t* __restrict__ seg_of, const int32_t* __restrict__ num_segments, char* __restrict__ centroids,
-    float* partial, uint32_t* counters, uint32_t N, uint32_t k, uint32_t cpr) {
+    float* partial, uint32_t* counters, uint32_t N, uint32_t k, uint32_t cpr, uint32_t mean) {
   constexpr int G = 64 / LPR;  // clusters handled side by side by one wave
   constexpr int E = Piece<DT>::kElems;
   const uint32_t S = (uint32_t)*num_segments;
@@ -213,9 +215,11 @@ __global__ __launch_bounds__(256) void centroid_kernel(
             }
           }
         }
-        const float fn = (float)n;
+        if (mean) {
+          const float fn = (float)n;
 #pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] /= fn;
+          for (int i = 0; i < E; ++i) acc[i] /= fn;
+        }
         store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
       }
     }
@@ -232,51 +236,51 @@ __global__ __launch_bounds__(256) void centroid_kernel(
     const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[sf + 1]);
     if (hi - lo > kCentroidWindow)
       long_cluster_window<DT>(tokens, perm, seg_offsets, centroids, partial, counters, sf, (int32_t)p0,
-                              min(hi, (int32_t)p1), 2 * wave, k, cpr, d);
+                              min(hi, (int32_t)p1), 2 * wave, k, cpr, d, mean);
   }
   if (sl != sf) {
     const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[sl]);
     const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[sl + 1]);
     if (hi - lo > kCentroidWindow)
       long_cluster_window<DT>(tokens, perm, seg_offsets, centroids, partial, counters, sl, lo, (int32_t)p1,
-                              2 * wave + 1, k, cpr, d);
+                              2 * wave + 1, k, cpr, d, mean);
   }
 }
 
 template <typename DT, int LPR>
 void launch_lpr(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
                 const int32_t* num_segments, void* centroids, float* partial, uint32_t* counters, int64_t N, int k,
-                uint32_t cpr, hipStream_t stream) {
+                uint32_t cpr, bool mean, hipStream_t stream) {
   constexpr int G = 64 / LPR;
   const uint64_t waves = ((uint64_t)N + G - 1) / G;  // worst case S == N; surplus waves leave at once
   const uint32_t blocks = (uint32_t)((waves + 3) / 4);
   hipLaunchKernelGGL((centroid_kernel<DT, LPR>), dim3(blocks), dim3(256), 0, stream, (const char*)tokens, perm,
                      seg_offsets, seg_of, num_segments, (char*)centroids, partial, counters, (uint32_t)N, (uint32_t)k,
-                     cpr);
+                     cpr, mean ? 1u : 0u);
 }
 
 template <typename DT>
 void launch_typed(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
                   const int32_t* num_segments, void* centroids, float* partial, uint32_t* counters, int64_t N, int k,
-                  uint32_t cpr, hipStream_t stream) {
+                  uint32_t cpr, bool mean, hipStream_t stream) {
   if (cpr > 16)
-    launch_lpr<DT, 64>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
+    launch_lpr<DT, 64>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, mean, stream);
   else if (cpr > 4)
-    launch_lpr<DT, 16>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
+    launch_lpr<DT, 16>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, mean, stream);
   else
-    launch_lpr<DT, 4>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
+    launch_lpr<DT, 4>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, mean, stream);
 }
 
 }  // namespace
 
 hipError_t launch_centroid(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
                            const int32_t* num_segments, void* centroids, float* partial, uint32_t* counters, int64_t N,
-                           int k, int d, bool bf16, hipStream_t stream) {
+                           int k, int d, bool bf16, bool mean, hipStream_t stream) {
   const uint32_t cpr = (uint32_t)((size_t)d * (bf16 ? 2 : 4) / 16);
   if (bf16)
-    launch_typed<BF16>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
+    launch_typed<BF16>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, mean, stream);
   else
-    launch_typed<F32>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, stream);
+    launch_typed<F32>(tokens, perm, seg_offsets, seg_of, num_segments, centroids, partial, counters, N, k, cpr, mean, stream);
   return hipGetLastError();
 }
 

@@ -46,11 +46,12 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
                         int32_t* seg_of, int32_t* num_segments, char* workspace, hipStream_t stream);
 
 // ---- step 3: centroid ---------------------------------------------------
+// Row of sorted position p is rows[perm[p] / k].  mean: divide each cluster's sum by its member count.
 // partial: 2 * ceil(N / kCentroidWindow) rows of d binary32 sums; counters: as many counts, zero on entry
 // (launch_group clears them).
-hipError_t launch_centroid(const void* tokens, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
+hipError_t launch_centroid(const void* rows, const int32_t* perm, const int32_t* seg_offsets, const int32_t* seg_of,
                            const int32_t* num_segments, void* centroids, float* partial, uint32_t* counters, int64_t N,
-                           int k, int d, bool bf16, hipStream_t stream);
+                           int k, int d, bool bf16, bool mean, hipStream_t stream);
 
 // ---- step 4: restore ----------------------------------------------------
 hipError_t launch_restore(const void* tokens, const void* centroids, const void* expert_out,
@@ -60,5 +61,16 @@ hipError_t launch_restore(const void* tokens, const void* centroids, const void*
 hipError_t launch_restore_combine(const void* tokens, const void* centroids, const void* expert_out,
                                   const int32_t* seg_of, const int32_t* seg_offsets, const float* gate_weight,
                                   void* out, int64_t T, int k, int d, bool bf16, uint32_t flags, hipStream_t stream);
+
+// ---- backward of steps 3 and 4 -------------------------------------------
+struct BackwardPlan {
+  size_t windows;  // window sums / counters of the segment sum
+  size_t off_partial, off_counters, total_bytes;
+};
+BackwardPlan plan_backward(int64_t N, int d);
+hipError_t launch_clear_counters(uint32_t* counters, size_t n, hipStream_t stream);
+hipError_t launch_grad_tokens(const void* grad_out, const void* grad_centroids, const void* grad_expert_out,
+                              const int32_t* seg_of, const int32_t* seg_offsets, void* grad_tokens, int64_t T, int k,
+                              int d, bool bf16, uint32_t flags, hipStream_t stream);
 
 }  // namespace lshmoe

@@ -147,3 +147,41 @@ def check_combine(run: GpuRun, tokens: np.ndarray, gate_weight: np.ndarray, k: i
     ref = oracle.restore_ref(tokens, run.centroids, run.expert_out, seg_of, k, dtype, no_residual=bool(flags & 1),
                              gate_weight=gate_weight)
     return assert_rows_close(got, ref, dtype, "restore+combine")
+
+
+def check_backward(run: GpuRun, T: int, d: int, k: int, dtype: str, seed: int, flags: int = 0):
+    """lshmoe_decompress_backward and lshmoe_compress_backward against the oracle's chain rule, on the clusters
+    of a finished run and seeded random gradients."""
+    N, S = T * k, run.S
+    rng = np.random.default_rng(seed)
+    from workloads import synth
+    gy = synth.f32_to_storage(rng.standard_normal((N, d)).astype(np.float32), dtype)
+    h = synth.f32_to_storage(rng.standard_normal((S, d)).astype(np.float32), dtype)
+    out = run.out
+    gy_t = to_device(gy, dtype).view(T, k, d)
+    G_t = torch.full((N, d), float("nan"), dtype=gy_t.dtype, device="cuda")
+    code = lsh.LSHMOE_F32 if dtype == "f32" else lsh.LSHMOE_BF16
+    ws = torch.empty(lsh.lshmoe_backward_workspace_bytes(T, d, k, code) + 256, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xA5)                                    # the call must not rely on what the workspace holds
+    lsh.lshmoe_decompress_backward(gy_t, out.perm, out.seg_offsets, out.seg_of, out.num_segments, G_t, ws)
+    torch.cuda.synchronize()
+    perm = out.perm.cpu().numpy()
+    seg_offsets = out.seg_offsets[:S + 1].cpu().numpy()
+    seg_of = out.seg_of.cpu().numpy()
+    G_gpu = to_storage(G_t[:S], dtype)
+    G_ref = oracle.restore_backward_ref(gy, perm, seg_offsets, dtype)
+    assert_rows_close(G_gpu, G_ref, dtype, "segment sum of the output gradient")
+    single = np.diff(seg_offsets) == 1
+    assert np.array_equal(G_gpu[single], gy[perm[seg_offsets[:-1]][single]]), "one-member sums must equal their row"
+    assert torch.isnan(G_t[S:].float()).all(), "rows beyond S must stay untouched"
+
+    h_t = torch.zeros((N, d), dtype=gy_t.dtype, device="cuda")
+    h_t[:S] = to_device(h, dtype)
+    gx_t = torch.full((T, d), float("nan"), dtype=gy_t.dtype, device="cuda")
+    if flags & 1:
+        lsh.lshmoe_compress_backward(None, h_t, None, out.seg_of, out.seg_offsets, k, gx_t, flags=flags)
+    else:
+        lsh.lshmoe_compress_backward(gy_t, h_t, G_t, out.seg_of, out.seg_offsets, k, gx_t, flags=flags)
+    torch.cuda.synchronize()
+    gx_ref = oracle.compress_backward_ref(gy, h, G_gpu, seg_of, seg_offsets, k, dtype, no_residual=bool(flags & 1))
+    return assert_rows_close(to_storage(gx_t, dtype), gx_ref, dtype, "token gradient")

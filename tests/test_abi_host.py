@@ -30,6 +30,7 @@ def _declared_symbols():
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
     assert {"lshmoe_hash", "lshmoe_compress", "lshmoe_decompress", "lshmoe_decompress_combine", "lshmoe_workspace_bytes",
+            "lshmoe_backward_workspace_bytes", "lshmoe_decompress_backward", "lshmoe_compress_backward",
             "lshmoe_status_string", "lshmoe_last_error", "lshmoe_abi_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -91,6 +92,18 @@ def test_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, None, 16, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, p, 16, 64, 2, 1, 4, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, p, 0, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_SHAPE
+    # backward
+    need = lsh.lshmoe_backward_workspace_bytes(16, 64, 2, lsh.LSHMOE_BF16)
+    assert 0 < need <= lsh.lshmoe_workspace_bytes(16, 64, 2, 4, 2, 8, lsh.LSHMOE_BF16)   # a compress workspace is enough
+    assert lib.lshmoe_decompress_backward(p, p, p, p, None, 16, 64, 2, 1, p, 0x1000, 1 << 20, None) == lsh.LSHMOE_ERR_NULL
+    assert lib.lshmoe_decompress_backward(p, p, p, p, p, 16, 64, 2, 1, p, None, 0, None) == lsh.LSHMOE_ERR_WORKSPACE
+    assert lib.lshmoe_decompress_backward(p, p, p, p, p, 16, 64, 2, 1, p, 0x1000, need - 1, None) == lsh.LSHMOE_ERR_WORKSPACE
+    assert lib.lshmoe_decompress_backward(p, p, p, p, p, 16, 60, 2, 1, p, 0x1000, 1 << 20, None) == lsh.LSHMOE_ERR_UNSUPPORTED
+    assert lib.lshmoe_decompress_backward(p, p, p, p, p, 16, 64, 0, 1, p, 0x1000, 1 << 20, None) == lsh.LSHMOE_ERR_SHAPE
+    assert lib.lshmoe_compress_backward(None, p, None, p, p, 16, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL
+    assert lib.lshmoe_compress_backward(p, p, p, p, None, 16, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL
+    assert lib.lshmoe_compress_backward(p, p, p, p, p, 16, 64, 2, 1, 8, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
+    assert lib.lshmoe_compress_backward(p, p, p, p, p, -3, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_SHAPE
 
 
 def test_binding_refuses_host_tensors():

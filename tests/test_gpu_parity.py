@@ -226,6 +226,38 @@ def test_fused_gate_weighted_combine_shapes(H, dtype, T, d, k, E):
     H.check_combine(run, tokens, ones, k, dtype)
 
 
+# ------------------------------------------------------------------ backward
+@pytest.mark.parametrize("name,T", [("tiny", None), ("gpt", 3000), ("t5", 2200), ("swin", 4000)])
+def test_backward_named(H, name, T):
+    cfg = synth.config(name) if T is None else synth.config(name, T=T, centers=max(8, synth.config(name).centers * T // synth.config(name).T))
+    w = synth.generate(cfg)
+    run = H.run_and_check(w.tokens, w.rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
+    H.check_backward(run, cfg.T, cfg.d, cfg.k, cfg.dtype, seed=31)
+    H.check_backward(run, cfg.T, cfg.d, cfg.k, cfg.dtype, seed=32, flags=1)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,d,k,E", [(700, 24, 3, 5), (333, 512, 1, 4), (50, 8, 4, 4), (1, 64, 1, 1)])
+def test_backward_shapes(H, dtype, T, d, k, E):
+    tokens, rot, expert = _rand_inputs(33, T, d, k, E, 2, 4, dtype, centers=6)
+    run = H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn)
+    H.check_backward(run, T, d, k, dtype, seed=34)
+    H.check_backward(run, T, d, k, dtype, seed=35, flags=1)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_long_clusters(H, dtype):
+    # the segment sum of clusters longer than a window goes through the window sums too
+    sizes = [128, 129, 1, 127, 256, 257, 3, 1000, 2, 5000, 131, 1, 1, 384, 640, 7, 2049]
+    T, d, E = sum(sizes), 136, 3
+    tokens, rot, _ = _rand_inputs(36, T, d, 1, E, 2, 16, dtype)
+    ids = np.empty(T, np.uint64)
+    ids[np.random.default_rng(37).permutation(T)] = np.repeat(np.arange(len(sizes)), sizes).astype(np.uint64)
+    expert = np.tile(np.array([[2, 0]], np.int32), (T, 1))
+    run = H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn, bucket_override=ids)
+    H.check_backward(run, T, d, 2, dtype, seed=38)
+
+
 def test_deterministic_across_runs(H):
     cfg = synth.config("gpt", T=4000, centers=300)
     w = synth.generate(cfg)
