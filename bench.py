@@ -210,6 +210,30 @@ def main():
     result["supplementary_fused_combine"] = {
         "decompress_combine_ms": comb_ms, "algorithmic_bytes": comb_bytes,
         "achieved_gbs": comb_bytes / (comb_ms * 1e-3) / 1e9 if comb_ms else None}
+    # supplementary: backward of the path (segment sums of dL/dY, then dL/dx), on random gradients
+    gy = torch.randn((T, k, d), device="cuda").to(tdt)
+    hc = torch.randn((N, d), device="cuda").to(tdt)
+    gec = torch.empty((N, d), dtype=tdt, device="cuda")
+    gx = torch.empty((T, d), dtype=tdt, device="cuda")
+    bws = torch.empty(lsh.lshmoe_backward_workspace_bytes(T, d, k, lsh.LSHMOE_F32 if cfg.dtype == "f32" else lsh.LSHMOE_BF16) + 256,
+                      dtype=torch.uint8, device="cuda")
+    evb = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(min(K, 50))]
+    for i, (e0, e1, e2) in enumerate(evb):
+        o = outs[i % copies]
+        e0.record()
+        lsh.lshmoe_decompress_backward(gy, o.perm, o.seg_offsets, o.seg_of, o.num_segments, gec, bws)
+        e1.record()
+        lsh.lshmoe_compress_backward(gy, hc, gec, o.seg_of, o.seg_offsets, k, gx)
+        e2.record()
+    torch.cuda.synchronize()
+    if len(evb) > 5:
+        seg_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1, _ in evb[5:]]))
+        gtok_ms = float(np.mean([e1.elapsed_time(e2) for _, e1, e2 in evb[5:]]))
+        seg_bytes = (N + S) * row + 4 * N + 4 * (S + 1)                       # N gradient rows read, S sums written
+        gtok_bytes = (S + T + n_multi_assign + n_multi_seg) * row + 4 * N + 4 * (S + 1)
+        result["supplementary_backward"] = {
+            "decompress_backward_ms": seg_ms, "decompress_backward_gbs": seg_bytes / (seg_ms * 1e-3) / 1e9,
+            "compress_backward_ms": gtok_ms, "compress_backward_gbs": gtok_bytes / (gtok_ms * 1e-3) / 1e9}
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample)
     else:

@@ -1,26 +1,29 @@
 // Grouping of assignments by (expert, bucket) (Alg. 1: dispatch, then split
 // each expert's tokens into clusters by bucket id).
 //
-// A stable least-significant-digit radix sort of the packed key
-// (expert << bbits | bucket) carrying the assignment index, up to 9 bits per
-// pass, followed by a head-flag pass that numbers the clusters.  Integer work
-// only; every result is deterministic.  The arrays are a few MB at most, so
-// the step is bound by launch latency, not by HBM: the design goal is few
-// kernels.
+// A stable sort of the packed key (expert << bbits | bucket) carrying the
+// assignment index, followed by a head-flag pass that numbers the clusters.
+// Integer work only; every result is deterministic.  The arrays are a few MB
+// at most, so the step is bound by launch latency, not by HBM: the design goal
+// is few kernels.  Three routes by size:
+//
+//  - up to kSmallMaxN assignments: everything in one workgroup and one launch.
+//  - up to kFusedMaxTiles tiles of 2048 (every paper-shaped layer): ONE global
+//    radix pass on the top 9 key bits (histogram kernel + scatter kernel; the
+//    histogram kernel writes the tile's digit counts as one row of a tile-major
+//    table and every scatter block derives its own output offsets from that
+//    small table, so there is no scan launch), then one launch in which every
+//    one of the 512 bins is sorted on the remaining bits by a workgroup of its
+//    own, then two launches that number the clusters: five launches whatever
+//    the key width.  (Before: a histogram and a scatter launch per 9 key bits.)
+//  - larger: least-significant-digit radix passes of histogram,
+//    single-workgroup scan of the (bin, tile) table and scatter.
 //
 // Ranks inside a tile of 2048 keys come from wave ballots: a wave of 64 keys
 // finds, for every lane, the lanes holding the same digit; tile order equals
-// element order, which keeps the sort stable.
-//
-// Small inputs (up to kFusedMaxTiles tiles; every paper-shaped layer): two
-// kernels per pass.  The histogram kernel writes the tile's digit counts as
-// one row of a tile-major table, and every scatter block derives its own
-// output offsets from that small table (sum of the rows before it, prefix
-// over the bins), so there is no scan launch.  (Accumulating the next pass's
+// element order, which keeps the sort stable.  (Accumulating the next pass's
 // table with global atomics from inside the scatter was measured slower than
 // the separate histogram launch: device-scope atomics cost ~8 us per pass.)
-// Large inputs: histogram, single-workgroup scan of the (bin, tile) table and
-// scatter per pass.
 #include "kernels.h"
 
 namespace lshmoe {
@@ -160,6 +163,7 @@ struct PassArgs {
   uint32_t mask;
   uint32_t nblk;
   const uint32_t* table;  // FUSED: tile-major counts of this pass; else the scanned bin-major offsets
+  uint32_t* bin_start;    // FUSED, optional: block 0 writes the first output position of every bin, then N
 };
 
 template <bool FIRST, bool FUSED>
@@ -247,6 +251,11 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource sr
     start[0] = block_exclusive_scan(total[0], wave_sum, half) + before[0];
     uint32_t unused;
     start[1] = half + block_exclusive_scan(total[1], wave_sum, unused) + before[1];
+    if (a.bin_start != nullptr && blockIdx.x == 0) {  // nothing comes before tile 0: its starts are the bins' starts
+      a.bin_start[threadIdx.x] = start[0];
+      a.bin_start[threadIdx.x + 256] = start[1];
+      if (threadIdx.x == 0) a.bin_start[kGroupBins] = N;
+    }
   } else {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -535,6 +544,175 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_group_kernel(KeySource
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Most-significant-digit route (up to kFusedMaxTiles tiles): ONE global pass on the top digit of the key
+// splits the assignments into up to 512 bins (stable, so a bin keeps ascending assignment order); every bin
+// is then sorted on the remaining key bits by one workgroup.  That replaces a histogram and a scatter
+// launch per further digit by a single launch.
+//   bin of at most kBinFast keys: rank by counting in LDS.  Thread i holds key i; its output position is
+//     the number of keys that are smaller, plus the equal keys before it (stable).  Quadratic, but on at
+//     most 1024 keys that a wave reads as LDS broadcasts, and independent of the key width.
+//   larger bin: least-significant-digit radix passes over the bin's range through the two global buffers,
+//     as the one-workgroup route does (each wave owns a slice; counts per (wave, digit); ballot ranks).
+struct BinSortArgs {
+  const uint32_t* bin_start;  // [bins + 1]
+  uint64_t* key[2];           // [0]: keys after the global pass; [1]: receives the sorted keys
+  int32_t* idx[2];            // [0]: assignment ids after the global pass; [1]: scratch
+  int32_t* perm;              // receives the sorted assignment ids
+  int passes;                 // odd: the last radix pass of a large bin lands in key[1] / perm
+  int shift[8], width[8];     // radix digits of the low key bits, least significant first
+  int sub_shift;              // a small bin's sub-bin is (key >> sub_shift) & sub_mask
+  uint32_t sub_mask;
+};
+
+constexpr int kBinFast = 1024;
+constexpr int kBinWaves = 4;
+constexpr int kBinThreads = kBinWaves * 64;
+constexpr int kBinItems = kBinFast / kBinThreads;  // keys of a small bin per thread
+constexpr int kSubBins = 256;                      // sub-bins of a small bin (the next 8 key bits)
+
+__global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
+  __shared__ uint32_t cnt[kBinWaves][kGroupBins];  // 8 KB; the small-bin path keeps its keys here
+  __shared__ uint32_t place_s[kBinFast];           // small bin: a key's place in the bin before sorting
+  __shared__ uint32_t sub_cnt[kSubBins], sub_base[kSubBins];
+  __shared__ uint32_t wave_sum[kBinWaves];
+  const uint32_t lo_bin = a.bin_start[blockIdx.x], hi_bin = a.bin_start[blockIdx.x + 1];
+  const uint32_t n = hi_bin - lo_bin;
+  if (n == 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  if (n <= (uint32_t)kBinFast) {
+    // Small bin.  The keys are first thrown into sub-bins by their next (up to) 8 bits with LDS counters, in
+    // whatever order they arrive; a key's rank is then the start of its sub-bin plus the number of keys
+    // of that sub-bin that come before it, by key and, among equal keys, by place in the bin (stable).
+    // Only keys that agree in those 8 bits are compared, a handful unless many keys are equal.
+    static_assert(sizeof(cnt) >= kBinFast * sizeof(uint64_t), "keys of a small bin fit in the count table");
+    static_assert(kSubBins == kBinThreads, "one sub-bin counter per thread");
+    uint64_t* key_s = reinterpret_cast<uint64_t*>(&cnt[0][0]);
+    uint64_t key[kBinItems];
+    int32_t idx[kBinItems];
+    uint32_t sub[kBinItems], slot[kBinItems];
+#pragma unroll
+    for (int q = 0; q < kBinItems; ++q) {
+      const uint32_t i = threadIdx.x + q * kBinThreads;
+      key[q] = 0;
+      idx[q] = 0;
+      if (i < n) {
+        key[q] = a.key[0][lo_bin + i];
+        idx[q] = a.idx[0][lo_bin + i];
+      }
+    }
+    sub_cnt[threadIdx.x] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kBinItems; ++q) {
+      sub[q] = (uint32_t)(key[q] >> a.sub_shift) & a.sub_mask;
+      if (threadIdx.x + q * kBinThreads < n) slot[q] = atomicAdd(&sub_cnt[sub[q]], 1u);
+    }
+    __syncthreads();
+    {
+      uint32_t unused;
+      sub_base[threadIdx.x] = block_exclusive_scan(sub_cnt[threadIdx.x], wave_sum, unused);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kBinItems; ++q) {
+      const uint32_t i = threadIdx.x + q * kBinThreads;
+      if (i < n) {
+        const uint32_t at = sub_base[sub[q]] + slot[q];
+        key_s[at] = key[q];
+        place_s[at] = i;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kBinItems; ++q) {
+      const uint32_t i = threadIdx.x + q * kBinThreads;
+      if (i < n) {
+        const uint32_t first = sub_base[sub[q]], m = sub_cnt[sub[q]];
+        uint32_t rank = first;
+        for (uint32_t t = 0; t < m; ++t) {
+          const uint64_t kj = key_s[first + t];
+          const uint32_t pj = place_s[first + t];
+          rank += (kj < key[q] || (kj == key[q] && pj < i)) ? 1u : 0u;
+        }
+        a.key[1][lo_bin + rank] = key[q];
+        a.perm[lo_bin + rank] = idx[q];
+      }
+    }
+    return;
+  }
+
+  // large bin: radix passes over [lo_bin, hi_bin)
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const uint32_t slice = ((n + kBinWaves - 1) / kBinWaves + 63u) & ~63u;  // keys per wave, whole rounds
+  const uint32_t lo = min(lo_bin + (uint32_t)wave * slice, hi_bin), hi = min(lo + slice, hi_bin);
+  for (int p = 0; p < a.passes; ++p) {
+    const bool last = p == a.passes - 1;
+    const int shift = a.shift[p];
+    const uint32_t mask = (1u << a.width[p]) - 1u;
+    const uint64_t* skey = a.key[p & 1];
+    const int32_t* sidx = a.idx[p & 1];
+    uint64_t* dkey = a.key[(p + 1) & 1];
+    int32_t* didx = last ? a.perm : a.idx[(p + 1) & 1];
+
+    for (int i = threadIdx.x; i < kBinWaves * kGroupBins; i += kBinThreads) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    for (uint32_t base = lo; base < hi; base += 256) {
+      uint64_t key[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) key[q] = skey[min(base + q * 64 + lane, hi_bin - 1)];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (base + q * 64 + lane < hi) atomicAdd(&cnt[wave][(uint32_t)(key[q] >> shift) & mask], 1u);
+    }
+    __syncthreads();
+    {  // counts -> start offsets, ordered by (digit, wave); two digits per thread
+      uint32_t c[2][kBinWaves], tot[2] = {0, 0};
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int w = 0; w < kBinWaves; ++w) {
+          c[j][w] = cnt[w][threadIdx.x + 256 * j];
+          tot[j] += c[j][w];
+        }
+      uint32_t half, unused;
+      uint32_t run0 = lo_bin + block_exclusive_scan(tot[0], wave_sum, half);
+      uint32_t run1 = lo_bin + half + block_exclusive_scan(tot[1], wave_sum, unused);
+#pragma unroll
+      for (int w = 0; w < kBinWaves; ++w) {
+        cnt[w][threadIdx.x] = run0;
+        run0 += c[0][w];
+        cnt[w][threadIdx.x + 256] = run1;
+        run1 += c[1][w];
+      }
+    }
+    __syncthreads();
+    for (uint32_t base = lo; base < hi; base += 64) {
+      const bool valid = base + lane < hi;
+      const uint32_t at = min(base + lane, hi_bin - 1);
+      const uint64_t key = skey[at];
+      const int32_t idx = sidx[at];
+      const uint32_t digit = (uint32_t)(key >> shift) & mask;
+      uint64_t same = __ballot(valid);
+#pragma unroll
+      for (int b = 0; b < kMaxDigitBits; ++b) {
+        const bool bit = (digit >> b) & 1u;
+        const uint64_t bal = __ballot(bit);
+        same &= bit ? bal : ~bal;
+      }
+      const uint32_t rank = (uint32_t)__popcll(same & lt_mask);
+      const uint32_t start = cnt[wave][digit];
+      if (valid) {
+        dkey[start + rank] = key;
+        didx[start + rank] = idx;
+        if (rank == 0) cnt[wave][digit] = start + (uint32_t)__popcll(same);  // after every lane of the round has read
+      }
+    }
+    __syncthreads();  // the pass's global writes are visible to the whole workgroup (one compute unit, one L1)
+  }
+}
+
 int bits_for(uint64_t max_value) {  // number of bits needed to hold max_value
   int b = 0;
   while (max_value) {
@@ -584,6 +762,22 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
   p.sort_blocks = (uint32_t)((p.N + kSortTile - 1) / kSortTile);
   p.seg_blocks = (uint32_t)((p.N + kSegTile - 1) / kSegTile);
   p.fused = p.sort_blocks <= (uint32_t)kFusedMaxTiles;
+  p.msd = p.fused && p.N > kSmallMaxN && bits > kMaxDigitBits;
+  if (p.msd) {
+    p.top_width = kMaxDigitBits;
+    p.top_shift = bits - kMaxDigitBits;
+    const int rem = p.top_shift;
+    int lp = (rem + kMaxDigitBits - 1) / kMaxDigitBits;
+    if (lp % 2 == 0) ++lp;  // an odd count leaves a large bin's result in the second buffer
+    p.low_passes = lp;
+    for (int i = 0, at = 0; i < lp; ++i) {
+      int w = (rem - at + (lp - i) - 1) / (lp - i);
+      if (w < 1) w = 1;  // more passes than bits: the surplus digits read zero bits above the key
+      p.low_shift[i] = at;
+      p.low_width[i] = w;
+      at += w;
+    }
+  }
   size_t off = 0;
   for (int i = 0; i < 2; ++i) {
     p.off_key[i] = off;
@@ -597,6 +791,8 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
   off = align256(off + (size_t)kGroupBins * p.sort_blocks * 4);
   p.off_blocksum = off;
   off = align256(off + ((size_t)p.seg_blocks + 1) * 4);
+  p.off_binstart = off;
+  off = align256(off + ((size_t)kGroupBins + 1) * 4);
   const size_t windows = 2 * (size_t)((p.N + kCentroidWindow - 1) / kCentroidWindow);
   p.off_partial = off;
   off = align256(off + windows * (size_t)d * 4);
@@ -639,7 +835,34 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     return hipGetLastError();
   }
   const uint64_t* sorted_key = nullptr;
-  for (int p = 0; p < plan.passes; ++p) {
+  if (plan.msd) {
+    uint32_t* bin_start = (uint32_t*)(ws + plan.off_binstart);
+    PassArgs a{};
+    a.shift = plan.top_shift;
+    a.mask = (1u << plan.top_width) - 1u;
+    a.nblk = nblk;
+    a.table = table;
+    a.bin_start = bin_start;
+    hipLaunchKernelGGL((sort_hist_kernel<true, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+    hipError_t e = launch_scatter<true, true>(src, N, a, keybuf[0], idxbuf[0], stream);
+    if (e != hipSuccess) return e;
+    BinSortArgs b{};
+    b.bin_start = bin_start;
+    b.key[0] = keybuf[0]; b.key[1] = keybuf[1];
+    b.idx[0] = idxbuf[0]; b.idx[1] = idxbuf[1];
+    b.perm = perm;
+    b.passes = plan.low_passes;
+    for (int p = 0; p < plan.low_passes; ++p) {
+      b.shift[p] = plan.low_shift[p];
+      b.width[p] = plan.low_width[p];
+    }
+    const int sub_bits = plan.top_shift < 8 ? plan.top_shift : 8;
+    b.sub_shift = plan.top_shift - sub_bits;
+    b.sub_mask = (1u << sub_bits) - 1u;
+    hipLaunchKernelGGL(bin_sort_kernel, dim3(1u << plan.top_width), dim3(kBinThreads), 0, stream, b);
+    sorted_key = keybuf[1];
+  }
+  for (int p = 0; p < (plan.msd ? 0 : plan.passes); ++p) {
     const bool last = p == plan.passes - 1;
     uint64_t* dkey = keybuf[p & 1];
     int32_t* didx = last ? perm : idxbuf[p & 1];
