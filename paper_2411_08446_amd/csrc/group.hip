@@ -37,6 +37,8 @@ constexpr int kGhStride = kGroupsPerTile + 1;          // per-bin row of group c
 constexpr int kTableBatch = 32;                        // count-table rows a thread fetches per round trip
 constexpr int kSegThreads = 256;
 constexpr int kSegItems = kSegTile / kSegThreads;     // 4
+constexpr int kSegTileBits = 10;
+static_assert((1 << kSegTileBits) == kSegTile, "kSegTileBits");
 
 struct KeySource {
   // pass 0 builds keys from the inputs; later passes read the ping-pong buffers
@@ -87,8 +89,12 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
 // bin-major table (scanned next).
 template <bool FIRST, bool FUSED>
 __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(KeySource src, uint32_t N, int shift, uint32_t mask,
-                                                                 uint32_t nblk, uint32_t* __restrict__ table) {
+                                                                 uint32_t nblk, uint32_t* __restrict__ table,
+                                                                 uint32_t* __restrict__ clear = nullptr,
+                                                                 uint32_t clear_n = 0) {
   __shared__ uint32_t h[kGroupBins];
+  if (clear != nullptr && blockIdx.x * kSortThreads + threadIdx.x < clear_n)  // counters a later kernel adds to
+    clear[blockIdx.x * kSortThreads + threadIdx.x] = 0;
   h[threadIdx.x] = 0;
   h[threadIdx.x + 256] = 0;
   __syncthreads();
@@ -158,12 +164,31 @@ __global__ __launch_bounds__(1024) void scan_kernel(uint32_t* __restrict__ data,
   }
 }
 
+constexpr int kBinChunk = 2048;  // most-significant-digit route: keys one workgroup sorts (see bin_sort_kernel)
+
+// The chunk table: written by block 0 of the global scatter from the bins' sizes.
+__device__ __forceinline__ void write_chunk_table(uint32_t total0, uint32_t total1, uint32_t* bin_start,
+                                                  uint32_t* chunk_tbl, uint32_t* wave_sum) {
+  const uint32_t c0 = (total0 + kBinChunk - 1) / kBinChunk, c1 = (total1 + kBinChunk - 1) / kBinChunk;
+  uint32_t half, rest;
+  const uint32_t at0 = block_exclusive_scan(c0, wave_sum, half);
+  const uint32_t at1 = half + block_exclusive_scan(c1, wave_sum, rest);
+  for (uint32_t j = 0; j < c0; ++j) chunk_tbl[at0 + j] = (threadIdx.x << 16) | j;
+  for (uint32_t j = 0; j < c1; ++j) chunk_tbl[at1 + j] = ((threadIdx.x + 256u) << 16) | j;
+  const int several = __syncthreads_or(c0 > 1 || c1 > 1);
+  if (threadIdx.x == 0) {
+    bin_start[kGroupBins + 1] = half + rest;
+    bin_start[kGroupBins + 2] = several ? 1u : 0u;
+  }
+}
+
 struct PassArgs {
   int shift;            // this pass's digit is (key >> shift) & mask
   uint32_t mask;
   uint32_t nblk;
   const uint32_t* table;  // FUSED: tile-major counts of this pass; else the scanned bin-major offsets
-  uint32_t* bin_start;    // FUSED, optional: block 0 writes the first output position of every bin, then N
+  uint32_t* bin_start;    // FUSED, optional: block 0 writes the first output position of every bin, then N,
+  uint32_t* chunk_tbl;    // then the number of chunks and whether a bin has several; and the chunk table
 };
 
 template <bool FIRST, bool FUSED>
@@ -255,6 +280,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource sr
       a.bin_start[threadIdx.x] = start[0];
       a.bin_start[threadIdx.x + 256] = start[1];
       if (threadIdx.x == 0) a.bin_start[kGroupBins] = N;
+      write_chunk_table(total[0], total[1], a.bin_start, a.chunk_tbl, wave_sum);
     }
   } else {
 #pragma unroll
@@ -335,8 +361,12 @@ template <bool SELF_PREFIX>
 __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(
     const uint64_t* __restrict__ key, const int32_t* __restrict__ perm, uint32_t N, uint32_t E, int bbits,
     const uint32_t* __restrict__ blocksum, int32_t* __restrict__ seg_offsets, int32_t* __restrict__ seg_expert,
-    int32_t* __restrict__ expert_offsets, int32_t* __restrict__ seg_of, int32_t* __restrict__ num_segments) {
+    int32_t* __restrict__ expert_offsets, int32_t* __restrict__ seg_of, int32_t* __restrict__ num_segments,
+    uint32_t* __restrict__ window_counters = nullptr) {
   __shared__ uint32_t wave_sum[kSegThreads / kWave];
+  constexpr uint32_t kCountersPerTile = 2 * kSegTile / kCentroidWindow;
+  if (window_counters != nullptr && threadIdx.x < kCountersPerTile)  // when no seg_count_kernel ran to clear them
+    window_counters[blockIdx.x * kCountersPerTile + threadIdx.x] = 0;
   uint32_t tiles_before = 0;
   if (SELF_PREFIX) {
     uint32_t part = 0;
@@ -546,47 +576,71 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_group_kernel(KeySource
 
 // ---------------------------------------------------------------------------------------------------
 // Most-significant-digit route (up to kFusedMaxTiles tiles): ONE global pass on the top digit of the key
-// splits the assignments into up to 512 bins (stable, so a bin keeps ascending assignment order); every bin
-// is then sorted on the remaining key bits by one workgroup.  That replaces a histogram and a scatter
-// launch per further digit by a single launch.
-//   bin of at most kBinFast keys: rank by counting in LDS.  Thread i holds key i; its output position is
-//     the number of keys that are smaller, plus the equal keys before it (stable).  Quadratic, but on at
-//     most 1024 keys that a wave reads as LDS broadcasts, and independent of the key width.
-//   larger bin: least-significant-digit radix passes over the bin's range through the two global buffers,
-//     as the one-workgroup route does (each wave owns a slice; counts per (wave, digit); ballot ranks).
+// splits the assignments into up to 512 bins (stable, so a bin keeps ascending assignment order).  A bin
+// is cut into chunks of at most kBinChunk consecutive keys; one workgroup sorts one chunk on the remaining
+// key bits inside LDS; a bin of several chunks is then merged by rank.  That replaces a histogram and a
+// scatter launch per further digit by one launch (two when some bin has more than kBinChunk keys).
+//
+// Chunk sort, two ways:
+//   up to kBinFast keys and no crowded sub-bin: the keys are thrown into sub-bins by their next (up to) 8
+//     bits with LDS counters, in whatever order they arrive; a key's rank is the start of its sub-bin plus
+//     the number of keys of that sub-bin that come before it, by key and, among equal keys, by place in the
+//     chunk (stable).  Only keys that agree in those 8 bits are compared: a handful.
+//   otherwise: least-significant-digit radix passes between two LDS buffers (each wave owns a slice of the
+//     chunk; counts per (wave, digit); ranks inside a round of 64 keys from wave ballots), the last pass
+//     writing to global memory.  Its cost does not depend on how many keys are equal.
 struct BinSortArgs {
-  const uint32_t* bin_start;  // [bins + 1]
+  const uint32_t* bin_start;  // [bins + 1], then [bins + 1] = number of chunks, [bins + 2] = 1 if a bin has several
+  const uint32_t* chunk_tbl;  // chunk w is chunk (entry & 0xffff) of bin (entry >> 16)
   uint64_t* key[2];           // [0]: keys after the global pass; [1]: receives the sorted keys
-  int32_t* idx[2];            // [0]: assignment ids after the global pass; [1]: scratch
+  int32_t* idx[2];            // [0]: assignment ids after the global pass
   int32_t* perm;              // receives the sorted assignment ids
-  int passes;                 // odd: the last radix pass of a large bin lands in key[1] / perm
-  int shift[8], width[8];     // radix digits of the low key bits, least significant first
-  int sub_shift;              // a small bin's sub-bin is (key >> sub_shift) & sub_mask
+  int passes;                 // radix passes over the low key bits
+  int shift[8], width[8];     // their digits, least significant first
+  int sub_shift;              // sub-bin of a key is (key >> sub_shift) & sub_mask
   uint32_t sub_mask;
+  uint32_t* tile_heads;       // [tiles of kSegTile positions]: cluster heads per tile, added to as bins are finished
 };
 
-constexpr int kBinFast = 1024;
+// Adds the heads counted in LDS per numbering tile (the chunk's positions touch at most kChunkTiles of them) to
+// the global per-tile counts.  Every thread of the workgroup calls it.
+constexpr int kChunkTiles = kBinChunk / kSegTile + 1;
+__device__ __forceinline__ void flush_tile_heads(const uint32_t* tile_cnt, uint32_t first_tile, uint32_t* tile_heads) {
+  __syncthreads();
+  if (threadIdx.x < (uint32_t)kChunkTiles && tile_cnt[threadIdx.x] != 0)
+    atomicAdd(&tile_heads[first_tile + threadIdx.x], tile_cnt[threadIdx.x]);
+}
+
+constexpr int kBinFast = 1024;                     // up to here the sub-bin way is tried first
 constexpr int kBinWaves = 4;
 constexpr int kBinThreads = kBinWaves * 64;
-constexpr int kBinItems = kBinFast / kBinThreads;  // keys of a small bin per thread
-constexpr int kSubBins = 256;                      // sub-bins of a small bin (the next 8 key bits)
+constexpr int kBinItems = kBinFast / kBinThreads;  // keys per thread on the sub-bin way
+constexpr int kSubBins = 256;
+constexpr uint32_t kSubBinCrowd = 32;              // a sub-bin with more keys sends the chunk the radix way
+constexpr size_t kBinSortLds = 2 * (size_t)kBinChunk * (8 + 4);  // two (key, id) buffers: 48 KB
 
 __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
-  __shared__ uint32_t cnt[kBinWaves][kGroupBins];  // 8 KB; the small-bin path keeps its keys here
-  __shared__ uint32_t place_s[kBinFast];           // small bin: a key's place in the bin before sorting
+  extern __shared__ uint64_t bin_lds[];            // radix way: keys [2][kBinChunk], then ids [2][kBinChunk]
+  __shared__ uint32_t cnt[kBinWaves][kGroupBins];  // 8 KB; the sub-bin way keeps its keys here
+  __shared__ uint32_t place_s[kBinFast];           // sub-bin way: a key's place in the chunk before sorting
   __shared__ uint32_t sub_cnt[kSubBins], sub_base[kSubBins];
   __shared__ uint32_t wave_sum[kBinWaves];
-  const uint32_t lo_bin = a.bin_start[blockIdx.x], hi_bin = a.bin_start[blockIdx.x + 1];
-  const uint32_t n = hi_bin - lo_bin;
-  if (n == 0) return;
+  __shared__ uint32_t tile_cnt[kChunkTiles];
+  if (blockIdx.x >= a.bin_start[kGroupBins + 1]) return;
+  if (threadIdx.x < (uint32_t)kChunkTiles) tile_cnt[threadIdx.x] = 0;  // a barrier follows on every way
+  const uint32_t entry = a.chunk_tbl[blockIdx.x];
+  const uint32_t bin = entry >> 16, chunk = entry & 0xffffu;
+  const uint32_t lo_bin = a.bin_start[bin], hi_bin = a.bin_start[bin + 1];
+  const uint32_t lo = lo_bin + chunk * kBinChunk, hi = min(lo + (uint32_t)kBinChunk, hi_bin);
+  const uint32_t n = hi - lo;
+  // a bin of one chunk is finished here; the chunks of a larger bin are sorted in place and merged afterwards
+  const bool alone = hi_bin - lo_bin <= (uint32_t)kBinChunk;
+  uint64_t* out_key = alone ? a.key[1] : a.key[0];
+  int32_t* out_idx = alone ? a.perm : a.idx[0];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   if (n <= (uint32_t)kBinFast) {
-    // Small bin.  The keys are first thrown into sub-bins by their next (up to) 8 bits with LDS counters, in
-    // whatever order they arrive; a key's rank is then the start of its sub-bin plus the number of keys
-    // of that sub-bin that come before it, by key and, among equal keys, by place in the bin (stable).
-    // Only keys that agree in those 8 bits are compared, a handful unless many keys are equal.
-    static_assert(sizeof(cnt) >= kBinFast * sizeof(uint64_t), "keys of a small bin fit in the count table");
+    static_assert(sizeof(cnt) >= kBinFast * sizeof(uint64_t), "keys of a small chunk fit in the count table");
     static_assert(kSubBins == kBinThreads, "one sub-bin counter per thread");
     uint64_t* key_s = reinterpret_cast<uint64_t*>(&cnt[0][0]);
     uint64_t key[kBinItems];
@@ -598,8 +652,8 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
       key[q] = 0;
       idx[q] = 0;
       if (i < n) {
-        key[q] = a.key[0][lo_bin + i];
-        idx[q] = a.idx[0][lo_bin + i];
+        key[q] = a.key[0][lo + i];
+        idx[q] = a.idx[0][lo + i];
       }
     }
     sub_cnt[threadIdx.x] = 0;
@@ -610,62 +664,69 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
       if (threadIdx.x + q * kBinThreads < n) slot[q] = atomicAdd(&sub_cnt[sub[q]], 1u);
     }
     __syncthreads();
-    {
-      uint32_t unused;
-      sub_base[threadIdx.x] = block_exclusive_scan(sub_cnt[threadIdx.x], wave_sum, unused);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < kBinItems; ++q) {
-      const uint32_t i = threadIdx.x + q * kBinThreads;
-      if (i < n) {
-        const uint32_t at = sub_base[sub[q]] + slot[q];
-        key_s[at] = key[q];
-        place_s[at] = i;
+    const uint32_t mine = sub_cnt[threadIdx.x];
+    const int crowded = __syncthreads_or(mine > kSubBinCrowd);
+    if (!crowded) {
+      {
+        uint32_t unused;
+        sub_base[threadIdx.x] = block_exclusive_scan(mine, wave_sum, unused);
       }
-    }
-    __syncthreads();
+      __syncthreads();
 #pragma unroll
-    for (int q = 0; q < kBinItems; ++q) {
-      const uint32_t i = threadIdx.x + q * kBinThreads;
-      if (i < n) {
-        const uint32_t first = sub_base[sub[q]], m = sub_cnt[sub[q]];
-        uint32_t rank = first;
-        for (uint32_t t = 0; t < m; ++t) {
-          const uint64_t kj = key_s[first + t];
-          const uint32_t pj = place_s[first + t];
-          rank += (kj < key[q] || (kj == key[q] && pj < i)) ? 1u : 0u;
+      for (int q = 0; q < kBinItems; ++q) {
+        const uint32_t i = threadIdx.x + q * kBinThreads;
+        if (i < n) {
+          const uint32_t at = sub_base[sub[q]] + slot[q];
+          key_s[at] = key[q];
+          place_s[at] = i;
         }
-        a.key[1][lo_bin + rank] = key[q];
-        a.perm[lo_bin + rank] = idx[q];
       }
+      __syncthreads();  // also: every key of the chunk has been read before the first one is written back
+#pragma unroll
+      for (int q = 0; q < kBinItems; ++q) {
+        const uint32_t i = threadIdx.x + q * kBinThreads;
+        if (i < n) {
+          const uint32_t first = sub_base[sub[q]], m = sub_cnt[sub[q]];
+          uint32_t rank = first;
+          bool repeat = false;  // an equal key comes before this one: not the head of its cluster
+          for (uint32_t t = 0; t < m; ++t) {
+            const uint64_t kj = key_s[first + t];
+            const uint32_t pj = place_s[first + t];
+            const bool eq_before = kj == key[q] && pj < i;
+            repeat |= eq_before;
+            rank += (kj < key[q] || eq_before) ? 1u : 0u;
+          }
+          out_key[lo + rank] = key[q];
+          out_idx[lo + rank] = idx[q];
+          if (alone && !repeat) atomicAdd(&tile_cnt[((lo + rank) >> kSegTileBits) - (lo >> kSegTileBits)], 1u);
+        }
+      }
+      if (alone) flush_tile_heads(tile_cnt, lo >> kSegTileBits, a.tile_heads);
+      return;
     }
-    return;
+    __syncthreads();  // the radix way below reuses cnt
   }
 
-  // large bin: radix passes over [lo_bin, hi_bin)
+  // radix way: the chunk lives in LDS between the passes
+  uint64_t* const kbuf = bin_lds;                                            // [2][kBinChunk]
+  int32_t* const ibuf = reinterpret_cast<int32_t*>(bin_lds + 2 * kBinChunk);  // [2][kBinChunk]
+  for (uint32_t i = threadIdx.x; i < n; i += kBinThreads) {
+    kbuf[i] = a.key[0][lo + i];
+    ibuf[i] = a.idx[0][lo + i];
+  }
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   const uint32_t slice = ((n + kBinWaves - 1) / kBinWaves + 63u) & ~63u;  // keys per wave, whole rounds
-  const uint32_t lo = min(lo_bin + (uint32_t)wave * slice, hi_bin), hi = min(lo + slice, hi_bin);
+  const uint32_t wlo = min((uint32_t)wave * slice, n), whi = min(wlo + slice, n);
   for (int p = 0; p < a.passes; ++p) {
-    const bool last = p == a.passes - 1;
     const int shift = a.shift[p];
     const uint32_t mask = (1u << a.width[p]) - 1u;
-    const uint64_t* skey = a.key[p & 1];
-    const int32_t* sidx = a.idx[p & 1];
-    uint64_t* dkey = a.key[(p + 1) & 1];
-    int32_t* didx = last ? a.perm : a.idx[(p + 1) & 1];
-
+    const uint64_t* skey = kbuf + (p & 1) * kBinChunk;
+    const int32_t* sidx = ibuf + (p & 1) * kBinChunk;
+    uint64_t* dkey = kbuf + ((p + 1) & 1) * kBinChunk;
+    int32_t* didx = ibuf + ((p + 1) & 1) * kBinChunk;
     for (int i = threadIdx.x; i < kBinWaves * kGroupBins; i += kBinThreads) (&cnt[0][0])[i] = 0;
-    __syncthreads();
-    for (uint32_t base = lo; base < hi; base += 256) {
-      uint64_t key[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) key[q] = skey[min(base + q * 64 + lane, hi_bin - 1)];
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (base + q * 64 + lane < hi) atomicAdd(&cnt[wave][(uint32_t)(key[q] >> shift) & mask], 1u);
-    }
+    __syncthreads();  // also: the chunk (first pass) or the previous pass's output is in LDS
+    for (uint32_t i = wlo + lane; i < whi; i += 64) atomicAdd(&cnt[wave][(uint32_t)(skey[i] >> shift) & mask], 1u);
     __syncthreads();
     {  // counts -> start offsets, ordered by (digit, wave); two digits per thread
       uint32_t c[2][kBinWaves], tot[2] = {0, 0};
@@ -677,8 +738,8 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
           tot[j] += c[j][w];
         }
       uint32_t half, unused;
-      uint32_t run0 = lo_bin + block_exclusive_scan(tot[0], wave_sum, half);
-      uint32_t run1 = lo_bin + half + block_exclusive_scan(tot[1], wave_sum, unused);
+      uint32_t run0 = block_exclusive_scan(tot[0], wave_sum, half);
+      uint32_t run1 = half + block_exclusive_scan(tot[1], wave_sum, unused);
 #pragma unroll
       for (int w = 0; w < kBinWaves; ++w) {
         cnt[w][threadIdx.x] = run0;
@@ -688,9 +749,9 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
       }
     }
     __syncthreads();
-    for (uint32_t base = lo; base < hi; base += 64) {
-      const bool valid = base + lane < hi;
-      const uint32_t at = min(base + lane, hi_bin - 1);
+    for (uint32_t base = wlo; base < whi; base += 64) {
+      const bool valid = base + lane < whi;
+      const uint32_t at = min(base + lane, n - 1);
       const uint64_t key = skey[at];
       const int32_t idx = sidx[at];
       const uint32_t digit = (uint32_t)(key >> shift) & mask;
@@ -709,8 +770,113 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
         if (rank == 0) cnt[wave][digit] = start + (uint32_t)__popcll(same);  // after every lane of the round has read
       }
     }
-    __syncthreads();  // the pass's global writes are visible to the whole workgroup (one compute unit, one L1)
+    __syncthreads();
   }
+  // the sorted chunk is in LDS: write it out in order and count the cluster heads
+  const uint64_t* fkey = kbuf + (a.passes & 1) * kBinChunk;
+  const int32_t* fidx = ibuf + (a.passes & 1) * kBinChunk;
+  for (uint32_t i = threadIdx.x; i < n; i += kBinThreads) {
+    const uint64_t k = fkey[i];
+    out_key[lo + i] = k;
+    out_idx[lo + i] = fidx[i];
+    if (alone && (i == 0 || fkey[i - 1] != k)) atomicAdd(&tile_cnt[((lo + i) >> kSegTileBits) - (lo >> kSegTileBits)], 1u);
+  }
+  if (alone) flush_tile_heads(tile_cnt, lo >> kSegTileBits, a.tile_heads);
+}
+
+// Merge of the sorted chunks of a bin that has several: the final place of a key is the bin's start plus
+// its place in its own chunk plus, for every other chunk of the bin, the number of keys there that come
+// before it: the smaller ones, and for an earlier chunk also the equal ones (chunks follow assignment
+// order, so this keeps the sort stable).  One workgroup per chunk; the other chunks pass through LDS one
+// at a time and are searched by bisection; kMergeSlices workgroups share the keys of one chunk, so that a
+// bin holding most of the input still spreads over the chip.  Leaves at once when no bin has several chunks.
+constexpr int kMergeSlices = 4;  // workgroups that share the keys of one chunk
+constexpr int kMergeOwn = kBinChunk / kMergeSlices / kBinThreads;  // keys per thread: 2
+
+__global__ __launch_bounds__(kBinThreads) void bin_merge_kernel(BinSortArgs a) {
+  __shared__ uint64_t other[kBinChunk];  // 16 KB
+  const uint32_t cidx = blockIdx.x / kMergeSlices, slice = blockIdx.x % kMergeSlices;
+  if (a.bin_start[kGroupBins + 2] == 0 || cidx >= a.bin_start[kGroupBins + 1]) return;
+  const uint32_t entry = a.chunk_tbl[cidx];
+  const uint32_t bin = entry >> 16, chunk = entry & 0xffffu;
+  const uint32_t lo_bin = a.bin_start[bin], hi_bin = a.bin_start[bin + 1];
+  if (hi_bin - lo_bin <= (uint32_t)kBinChunk) return;
+  const uint32_t chunks = (hi_bin - lo_bin + kBinChunk - 1) / kBinChunk;
+  const uint32_t lo = lo_bin + chunk * kBinChunk, hi = min(lo + (uint32_t)kBinChunk, hi_bin);
+  const uint32_t n = hi - lo;
+  constexpr int kItems = kBinChunk / kBinThreads;  // keys of another chunk a thread stages: 8
+  uint64_t key[kMergeOwn];
+  uint32_t before[kMergeOwn];
+  bool repeat[kMergeOwn];
+#pragma unroll
+  for (int q = 0; q < kMergeOwn; ++q) {
+    const uint32_t i = slice * (kBinChunk / kMergeSlices) + threadIdx.x + q * kBinThreads;
+    key[q] = i < n ? a.key[0][lo + i] : 0;
+    before[q] = i;  // keys before it in its own chunk
+    repeat[q] = i < n && i > 0 && a.key[0][lo + i - 1] == key[q];
+  }
+  // the other chunks pass through LDS one at a time; the next one is fetched into registers while the
+  // current one is searched
+  auto fetch = [&](uint32_t c, uint64_t (&v)[kItems]) {
+    const uint32_t olo = lo_bin + c * kBinChunk, on = min((uint32_t)kBinChunk, hi_bin - olo);
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+      const uint32_t i = threadIdx.x + q * kBinThreads;
+      v[q] = a.key[0][olo + min(i, on - 1)];
+    }
+  };
+  auto next_other = [&](uint32_t c) { return c + 1 == chunk ? c + 2 : c + 1; };
+  uint64_t staged[kItems];
+  uint32_t c = chunk == 0 ? 1u : 0u;
+  fetch(c, staged);
+  for (; c < chunks; c = next_other(c)) {
+    const uint32_t on = min((uint32_t)kBinChunk, hi_bin - (lo_bin + c * kBinChunk));
+    __syncthreads();  // the previous chunk has been searched
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) other[threadIdx.x + q * kBinThreads] = staged[q];
+    __syncthreads();
+    if (next_other(c) < chunks) fetch(next_other(c), staged);
+    const bool earlier = c < chunk;
+    // number of keys of the other chunk that are < key (later chunk) or <= key (earlier chunk): bisection
+    // with a fixed number of steps, the thread's keys side by side so that the LDS reads overlap
+    uint32_t pos[kMergeOwn];
+#pragma unroll
+    for (int q = 0; q < kMergeOwn; ++q) pos[q] = 0;
+    for (uint32_t step = kBinChunk; step >= 1; step >>= 1) {
+#pragma unroll
+      for (int q = 0; q < kMergeOwn; ++q) {
+        const uint32_t t = pos[q] + step;
+        const uint64_t v = other[min(t, on) - 1];
+        const bool take = t <= on && (earlier ? v <= key[q] : v < key[q]);
+        pos[q] = take ? t : pos[q];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < kMergeOwn; ++q) {
+      before[q] += pos[q];
+      if (earlier && pos[q] > 0 && other[pos[q] - 1] == key[q]) repeat[q] = true;  // an equal key in an earlier chunk
+    }
+  }
+  // the keys land anywhere in the bin: heads are counted per numbering tile in LDS first
+  __syncthreads();
+  uint32_t* tile_cnt = reinterpret_cast<uint32_t*>(other);
+  const uint32_t first_tile = lo_bin >> kSegTileBits, tiles = ((hi_bin - 1) >> kSegTileBits) - first_tile + 1;
+  static_assert(sizeof(other) >= (kFusedMaxTiles * kSortTile / kSegTile) * sizeof(uint32_t), "tile counters fit");
+  for (uint32_t t = threadIdx.x; t < tiles; t += kBinThreads) tile_cnt[t] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < kMergeOwn; ++q) {
+    const uint32_t i = slice * (kBinChunk / kMergeSlices) + threadIdx.x + q * kBinThreads;
+    if (i < n) {
+      const uint32_t at = lo_bin + before[q];
+      a.key[1][at] = key[q];
+      a.perm[at] = a.idx[0][lo + i];
+      if (!repeat[q]) atomicAdd(&tile_cnt[(at >> kSegTileBits) - first_tile], 1u);
+    }
+  }
+  __syncthreads();
+  for (uint32_t t = threadIdx.x; t < tiles; t += kBinThreads)
+    if (tile_cnt[t] != 0) atomicAdd(&a.tile_heads[first_tile + t], tile_cnt[t]);
 }
 
 int bits_for(uint64_t max_value) {  // number of bits needed to hold max_value
@@ -767,12 +933,10 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
     p.top_width = kMaxDigitBits;
     p.top_shift = bits - kMaxDigitBits;
     const int rem = p.top_shift;
-    int lp = (rem + kMaxDigitBits - 1) / kMaxDigitBits;
-    if (lp % 2 == 0) ++lp;  // an odd count leaves a large bin's result in the second buffer
+    const int lp = (rem + kMaxDigitBits - 1) / kMaxDigitBits;
     p.low_passes = lp;
     for (int i = 0, at = 0; i < lp; ++i) {
-      int w = (rem - at + (lp - i) - 1) / (lp - i);
-      if (w < 1) w = 1;  // more passes than bits: the surplus digits read zero bits above the key
+      const int w = (rem - at + (lp - i) - 1) / (lp - i);
       p.low_shift[i] = at;
       p.low_width[i] = w;
       at += w;
@@ -792,7 +956,9 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
   p.off_blocksum = off;
   off = align256(off + ((size_t)p.seg_blocks + 1) * 4);
   p.off_binstart = off;
-  off = align256(off + ((size_t)kGroupBins + 1) * 4);
+  off = align256(off + ((size_t)kGroupBins + 3) * 4);
+  p.off_chunktbl = off;
+  off = align256(off + ((size_t)kGroupBins + p.sort_blocks) * 4);  // a chunk per non-empty bin and per kBinChunk keys
   const size_t windows = 2 * (size_t)((p.N + kCentroidWindow - 1) / kCentroidWindow);
   p.off_partial = off;
   off = align256(off + windows * (size_t)d * 4);
@@ -843,13 +1009,17 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     a.nblk = nblk;
     a.table = table;
     a.bin_start = bin_start;
-    hipLaunchKernelGGL((sort_hist_kernel<true, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+    a.chunk_tbl = (uint32_t*)(ws + plan.off_chunktbl);
+    // the histogram kernel also clears the per-tile head counts that the bin kernels add to
+    hipLaunchKernelGGL((sort_hist_kernel<true, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table,
+                       blocksum, plan.seg_blocks + 1);
     hipError_t e = launch_scatter<true, true>(src, N, a, keybuf[0], idxbuf[0], stream);
     if (e != hipSuccess) return e;
     BinSortArgs b{};
     b.bin_start = bin_start;
+    b.chunk_tbl = a.chunk_tbl;
     b.key[0] = keybuf[0]; b.key[1] = keybuf[1];
-    b.idx[0] = idxbuf[0]; b.idx[1] = idxbuf[1];
+    b.idx[0] = idxbuf[0];
     b.perm = perm;
     b.passes = plan.low_passes;
     for (int p = 0; p < plan.low_passes; ++p) {
@@ -859,8 +1029,16 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     const int sub_bits = plan.top_shift < 8 ? plan.top_shift : 8;
     b.sub_shift = plan.top_shift - sub_bits;
     b.sub_mask = (1u << sub_bits) - 1u;
-    hipLaunchKernelGGL(bin_sort_kernel, dim3(1u << plan.top_width), dim3(kBinThreads), 0, stream, b);
-    sorted_key = keybuf[1];
+    b.tile_heads = blocksum;
+    static_assert(kBinChunk == kSortTile, "the chunk bound below counts sort tiles");
+    const dim3 chunks((uint32_t)kGroupBins + nblk), threads(kBinThreads);
+    hipLaunchKernelGGL(bin_sort_kernel, chunks, threads, kBinSortLds, stream, b);
+    hipLaunchKernelGGL(bin_merge_kernel, dim3(chunks.x * kMergeSlices), threads, 0, stream, b);
+    // the heads per numbering tile are known: number the clusters (the tile count is within kSelfPrefixMaxTiles here)
+    hipLaunchKernelGGL(seg_write_kernel<true>, dim3(plan.seg_blocks), dim3(kSegThreads), 0, stream,
+                       (const uint64_t*)keybuf[1], perm, N, (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert,
+                       expert_offsets, seg_of, num_segments, (uint32_t*)(ws + plan.off_counters));
+    return hipGetLastError();
   }
   for (int p = 0; p < (plan.msd ? 0 : plan.passes); ++p) {
     const bool last = p == plan.passes - 1;

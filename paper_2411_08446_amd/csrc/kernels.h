@@ -30,12 +30,12 @@ struct GroupPlan {
   bool fused;            // scatter blocks derive their offsets themselves (small inputs)
   bool msd;              // one global pass on the top digit, then every bin sorted by one workgroup
   int top_shift, top_width;        // msd: the global pass's digit
-  int low_passes;                  // msd: radix passes a large bin makes over the remaining bits (odd)
+  int low_passes;                  // msd: radix passes over the remaining bits
   int low_shift[8], low_width[8];
   uint32_t sort_blocks;  // tiles of kSortTile assignments
   uint32_t seg_blocks;   // tiles of kSegTile sorted positions
   // byte offsets into the workspace
-  size_t off_key[2], off_idx[2], off_table, off_blocksum, off_binstart;
+  size_t off_key[2], off_idx[2], off_table, off_blocksum, off_binstart, off_chunktbl;
   size_t off_partial, off_counters;  // window sums and window counters of the centroid step
   size_t total_bytes;
 };
