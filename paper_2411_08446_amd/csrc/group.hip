@@ -12,10 +12,13 @@
 //    radix pass on the top 9 key bits (histogram kernel + scatter kernel; the
 //    histogram kernel writes the tile's digit counts as one row of a tile-major
 //    table and every scatter block derives its own output offsets from that
-//    small table, so there is no scan launch), then one launch in which every
-//    one of the 512 bins is sorted on the remaining bits by a workgroup of its
-//    own, then two launches that number the clusters: five launches whatever
-//    the key width.  (Before: a histogram and a scatter launch per 9 key bits.)
+//    small table, so there is no scan launch), then one launch that sorts every
+//    bin on the remaining bits inside LDS (in chunks of 2048 keys), one launch
+//    that merges the chunks of bins that have several (it leaves at once when
+//    there are none), and one launch that numbers the clusters from the head
+//    counts the two bin kernels left per tile: five launches whatever the key
+//    width.  (Before: a histogram and a scatter launch per 9 key bits, and a
+//    counting launch.)
 //  - larger: least-significant-digit radix passes of histogram,
 //    single-workgroup scan of the (bin, tile) table and scatter.
 //
