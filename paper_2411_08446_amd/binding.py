@@ -22,6 +22,7 @@ LSHMOE_ERR_HIP = 5
 LSHMOE_F32 = 0
 LSHMOE_BF16 = 1
 LSHMOE_FLAG_NO_RESIDUAL = 1
+ABI_VERSION = 3   # of include/lshmoe.h as this binding declares it
 
 
 class LshmoeError(RuntimeError):
@@ -50,6 +51,9 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.lshmoe_last_error.argtypes = []
     lib.lshmoe_abi_version.restype = ctypes.c_int
     lib.lshmoe_abi_version.argtypes = []
+    if lib.lshmoe_abi_version() != ABI_VERSION:
+        raise ImportError("%s has ABI version %d, this binding expects %d: rebuild it with "
+                          "`python -m paper_2411_08446_amd.build`" % (path, lib.lshmoe_abi_version(), ABI_VERSION))
     lib.lshmoe_workspace_bytes.restype = ctypes.c_int
     lib.lshmoe_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
     lib.lshmoe_hash.restype = ctypes.c_int

@@ -27,6 +27,8 @@
 // element order, which keeps the sort stable.  (Accumulating the next pass's
 // table with global atomics from inside the scatter was measured slower than
 // the separate histogram launch: device-scope atomics cost ~8 us per pass.)
+#include <atomic>
+
 #include "kernels.h"
 
 namespace lshmoe {
@@ -899,11 +901,11 @@ template <bool FIRST, bool FUSED>
 hipError_t launch_scatter(const KeySource& src, uint32_t N, const PassArgs& a, uint64_t* dkey, int32_t* didx,
                           hipStream_t stream) {
   auto kern = sort_scatter_kernel<FIRST, FUSED>;
-  static bool raised = false;  // benign race: the attribute is idempotent
-  if (!raised) {
+  static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
+  if (!raised.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLds);
     if (e != hipSuccess) return e;
-    raised = true;
+    raised.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(kern, dim3(a.nblk), dim3(kSortThreads), kScatterLds, stream, src, N, a, dkey, didx);
   return hipSuccess;

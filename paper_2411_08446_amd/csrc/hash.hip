@@ -29,6 +29,8 @@
 // Both MFMA operands take their k values with the same (lane, element) -> k
 // mapping, so which k a lane supplies is free as long as A and B agree: the
 // lane half h = l/32 takes piece 2s + h of the chunk in step s.
+#include <atomic>
+
 #include "kernels.h"
 
 namespace lshmoe {
@@ -294,11 +296,11 @@ hipError_t launch_one(const char* x, const char* R, uint64_t* bucket, int64_t T,
   static_assert(lds_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
   auto kern = hash_kernel<DT, MT, NTK, XDEPTH, WAVES, OCC, ALIGNED8, KTAIL>;
   if (lds_bytes > 48 * 1024) {
-    static bool raised = false;            // benign race: the attribute is idempotent
-    if (!raised) {
+    static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
+    if (!raised.load(std::memory_order_acquire)) {
       hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
       if (e != hipSuccess) return e;
-      raised = true;
+      raised.store(true, std::memory_order_release);
     }
   }
   const dim3 grid((uint32_t)((T + kBlockTokens - 1) / kBlockTokens)), block(WAVES * 64);
