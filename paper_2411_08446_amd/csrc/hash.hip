@@ -288,6 +288,233 @@ __global__ __launch_bounds__(WAVES * 64, OCC) void hash_kernel(const char* __res
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Variant for the widest hash groups (193..256 rows of R) on large inputs.  With eight 32-row tiles and one
+// 32-token tile per wave, every MFMA needs a fresh A fragment from LDS, which is exactly the LDS read peak
+// (1 KB per 32-cycle MFMA and SIMD), and the direct token loads (32 bytes of 32 different rows per
+// instruction) load the address path.  Here a wave keeps 4 row tiles x 2 token tiles instead: 8 waves = 4
+// token groups of 64 x 2 halves of the rows.  Per MFMA step a wave reads 4 A and 2 B fragments for 8 MFMAs
+// (0.75 KB per MFMA), and the tokens are staged through LDS like R, with full-line coalesced global loads
+// that write LDS directly: the two waves that share a token group read them from LDS, not twice from memory.  The two row halves of
+// a token are joined at the end through LDS.
+// Requires: r a multiple of 8, rows a whole number of 128-byte chunks.
+// 16 bytes per lane straight from global memory into LDS: lane l's piece lands at dst + l (dst is wave-uniform).
+// Written as inline assembly on purpose: for the compiler's own builtin the wait-count pass holds every later
+// LDS read until the load has landed, which would serialise the staging with the MFMA loop.  The caller
+// waits for these loads itself (s_waitcnt vmcnt) before the barrier that publishes the buffer.
+__device__ __forceinline__ void load16_to_lds(const char* src, uint4* dst) {
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)dst);
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
+}
+
+constexpr int kSplitWaves = 8, kSplitRows = 256, kSplitTokens = 256;
+constexpr int kSplitSlotsR = kSplitRows * kPieces, kSplitSlotsX = kSplitTokens * kPieces;  // 16-byte slots per buffer (32 KB each)
+constexpr int kSplitBufR = 2, kSplitBufX = 3;  // R comes from L2, one chunk ahead; the tokens from HBM, two chunks ahead
+
+template <typename DT>
+__global__ __launch_bounds__(kSplitWaves * 64, 1) void hash_split_kernel(
+    const char* __restrict__ tokens, const char* __restrict__ rot, uint64_t* __restrict__ bucket, uint32_t T,
+    int row_pieces, int L, int r, int hpg) {
+  constexpr int MTW = 4, NTW = 2;            // tiles per wave: rows x tokens
+  constexpr int TH = kSplitWaves * 64;
+  constexpr int LS = kSplitRows * kPieces / TH;  // staging loads per thread, chunk and operand: 4
+  extern __shared__ uint4 lds[];             // R chunks [kSplitBufR][kSplitSlotsR], then token chunks [kSplitBufX][kSplitSlotsX]
+  const int tid = threadIdx.x;
+  __builtin_assume(tid >= 0 && tid < TH);
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, h = lane >> 5;
+  const int g = wave >> 1, mh = wave & 1;    // token group, half of the rows
+  const uint32_t row_bytes = (uint32_t)row_pieces * 16u;
+  const int nchunks = row_pieces / kPieces;
+  const uint32_t tok_blk = blockIdx.x * (uint32_t)kSplitTokens;
+  const char* x_blk = tokens + (size_t)tok_blk * row_bytes;
+
+  // Staging uses the direct global->LDS load: a wave's instruction drops 64 x 16 bytes at consecutive LDS
+  // slots (lane l at slot base + l), i.e. 8 rows x 8 pieces; the swizzle is applied by choosing which piece of
+  // the row a lane fetches.  No staging registers and no LDS write instructions.
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const int sub = lane >> 3, pc = (lane & 7) ^ sub;   // row inside the 8-row group, logical piece this lane fetches
+  uint32_t off_x[LS];
+#pragma unroll
+  for (int i = 0; i < LS; ++i)               // token rows past the end re-read the last token
+    off_x[i] = (min(tok_blk + (uint32_t)(32 * wv + 8 * i + sub), T - 1) - tok_blk) * row_bytes + pc * 16;
+  int fslot[kSteps];
+#pragma unroll
+  for (int s = 0; s < kSteps; ++s) fslot[s] = n * kPieces + swizzle(n, 2 * s + h);
+  const int a_tile0 = mh * MTW * 32 * kPieces;   // first slot of this wave's row tiles inside an R buffer
+  const int b_tile0 = g * NTW * 32 * kPieces;    // ... and of its token tiles inside a token buffer
+  uint4* const lds_x = lds + kSplitBufR * kSplitSlotsR;
+
+  uint64_t b[NTW] = {0, 0};
+  for (int l0 = 0; l0 < L; l0 += hpg) {
+    const int nh = min(hpg, L - l0);
+    const int rows = nh * r;                 // valid rows of R in this group; staging rows past them repeat the last
+    const char* rot_group = rot + (size_t)l0 * r * row_bytes;
+    uint32_t off_a[LS];
+#pragma unroll
+    for (int i = 0; i < LS; ++i) off_a[i] = (uint32_t)min(32 * wv + 8 * i + sub, rows - 1) * row_bytes + pc * 16;
+
+    auto stage_r = [&](int chunk) {
+      uint4* dst = lds + (chunk % kSplitBufR) * kSplitSlotsR + (32 * wv) * kPieces;
+#pragma unroll
+      for (int i = 0; i < LS; ++i) load16_to_lds(rot_group + (size_t)chunk * (kPieces * 16) + off_a[i], dst + 8 * i * kPieces);
+    };
+    auto stage_x = [&](int chunk) {
+      uint4* dst = lds_x + (chunk % kSplitBufX) * kSplitSlotsX + (32 * wv) * kPieces;
+#pragma unroll
+      for (int i = 0; i < LS; ++i) load16_to_lds(x_blk + (size_t)chunk * (kPieces * 16) + off_x[i], dst + 8 * i * kPieces);
+    };
+
+    floatx16 acc[MTW][NTW];
+#pragma unroll
+    for (int t = 0; t < MTW; ++t)
+#pragma unroll
+      for (int u = 0; u < NTW; ++u)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[t][u][j] = 0.0f;
+
+    __syncthreads();                         // previous group's readers are done with LDS
+    stage_r(0);
+    stage_x(0);
+    if (nchunks > 1) stage_x(1);
+    // direct loads complete in issue order: all but the newest LS (the second token chunk) have landed
+    if (nchunks > 1) __builtin_amdgcn_s_waitcnt(0x0f70 | LS); else __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+      // buffers written now were last read in chunk c - 1, whose closing barrier every wave has passed
+      if (c + 1 < nchunks) stage_r(c + 1);
+      if (c + 2 < nchunks) stage_x(c + 2);
+      const uint4* bufa = lds + (c % kSplitBufR) * kSplitSlotsR;
+      const uint4* bufb = lds_x + (c % kSplitBufX) * kSplitSlotsX;
+      uint4 fa[2][MTW], fb[2][NTW];          // fragments of the step in flight and of the next one
+#pragma unroll
+      for (int t = 0; t < MTW; ++t) fa[0][t] = bufa[a_tile0 + t * 32 * kPieces + fslot[0]];
+#pragma unroll
+      for (int u = 0; u < NTW; ++u) fb[0][u] = bufb[b_tile0 + u * 32 * kPieces + fslot[0]];
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        if (s + 1 < kSteps) {
+#pragma unroll
+          for (int t = 0; t < MTW; ++t) fa[(s + 1) & 1][t] = bufa[a_tile0 + t * 32 * kPieces + fslot[s + 1]];
+#pragma unroll
+          for (int u = 0; u < NTW; ++u) fb[(s + 1) & 1][u] = bufb[b_tile0 + u * 32 * kPieces + fslot[s + 1]];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < MTW; ++t)
+#pragma unroll
+          for (int u = 0; u < NTW; ++u) Mma<DT>::run(fa[s & 1][t], fb[s & 1][u], acc[t][u]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // chunk c + 1 must have landed: everything but the LS newest loads (token chunk c + 2, when there is one)
+      if (c + 2 < nchunks) __builtin_amdgcn_s_waitcnt(0x0f70 | LS); else __builtin_amdgcn_s_waitcnt(0x0f70);
+      __syncthreads();
+    }
+
+    // Signed arg-max per hash over the rows this wave holds (tiles mh*4 .. mh*4+3), then joined with the other
+    // half of the rows through LDS.  Same two-pass integer scheme as hash_kernel's aligned epilogue.
+    uint2* ex = reinterpret_cast<uint2*>(lds);   // [kSplitTokens][nh]: {magnitude bits, row | sign << 31} of the upper half
+    uint32_t best_s[NTW], code_s[NTW];
+    for (int lh = 0; lh < nh; ++lh) {
+      const int lo = lh * r;
+#pragma unroll
+      for (int u = 0; u < NTW; ++u) {
+        int pmax = (int)0x80000000;
+        uint32_t nmax = 0;
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+          const int row0 = (mh * MTW + t) * 32;
+          if (row0 + 31 < lo || row0 >= lo + r) continue;  // wave-uniform
+#pragma unroll
+          for (int jb = 0; jb < 4; ++jb) {
+            const int base = row0 + 8 * jb - lo;
+            if (base < 0 || base >= r) continue;           // wave-uniform
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const uint32_t vi = __float_as_uint(acc[t][u][4 * jb + i]);
+              pmax = max(pmax, (int)vi);
+              nmax = max(nmax, vi);
+            }
+          }
+        }
+        const uint32_t mp = pmax >= 0 ? (uint32_t)pmax : 0u;
+        const uint32_t mn = (nmax >> 31) ? (nmax & 0x7fffffffu) : 0u;
+        uint32_t best = max(mp, mn);
+        bool neg = mn > mp;
+        const float bestf = __uint_as_float(best);
+        int bi = 0x7fffffff;
+        uint32_t wbits = neg ? 0x80000000u : 0u;           // pattern of the value at the lowest row of largest magnitude
+#pragma unroll
+        for (int t = MTW - 1; t >= 0; --t) {
+          const int row0 = (mh * MTW + t) * 32;
+          if (row0 + 31 < lo || row0 >= lo + r) continue;
+#pragma unroll
+          for (int jb = 3; jb >= 0; --jb) {
+            const int base = row0 + 8 * jb - lo;
+            if (base < 0 || base >= r) continue;
+#pragma unroll
+            for (int i = 3; i >= 0; --i) {
+              const float v = acc[t][u][4 * jb + i];
+              if (fabsf(v) == bestf) {
+                bi = base + 4 * h + i;
+                wbits = __float_as_uint(v);
+              }
+            }
+          }
+        }
+        if (mp == mn && best != 0u) neg = (wbits >> 31) != 0u;  // +m and -m both present: the lowest row decides
+        // the other 16 rows of each tile sit in lane l ^ 32
+        const uint32_t obest = (uint32_t)__shfl_xor((int)best, 32, 64);
+        const int obi = __shfl_xor(bi, 32, 64);
+        const int oneg = __shfl_xor((int)neg, 32, 64);
+        if (obest > best || (obest == best && obi < bi)) {
+          best = obest;
+          bi = obi;
+          neg = oneg != 0;
+        }
+        best_s[u] = best;
+        code_s[u] = (uint32_t)bi | (neg ? 0x80000000u : 0u);
+        if (mh == 1 && h == 0) ex[(g * NTW * 32 + u * 32 + n) * nh + lh] = make_uint2(best, code_s[u]);
+      }
+      __syncthreads();                       // the upper halves are in LDS (every wave reaches this: nh is uniform)
+      if (mh == 0) {
+#pragma unroll
+        for (int u = 0; u < NTW; ++u) {
+          const uint2 o = ex[(g * NTW * 32 + u * 32 + n) * nh + lh];
+          uint32_t code = code_s[u];
+          // rows of the upper half are higher, so on equal magnitude the lower half wins unless it holds no row
+          if (o.x > best_s[u] || (o.x == best_s[u] && (o.y & 0x7fffffffu) < (code & 0x7fffffffu))) code = o.y;
+          b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)((code & 0x7fffffffu) + ((code >> 31) ? (uint32_t)r : 0u));
+        }
+      }
+    }
+  }
+  if (mh == 0 && h == 0) {
+#pragma unroll
+    for (int u = 0; u < NTW; ++u) {
+      const uint32_t tok = tok_blk + (uint32_t)(g * NTW * 32 + u * 32 + n);
+      if (tok < T) bucket[tok] = b[u];
+    }
+  }
+}
+
+template <typename DT>
+hipError_t launch_split(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
+                        hipStream_t stream) {
+  constexpr size_t lds_bytes = ((size_t)kSplitBufR * kSplitSlotsR + (size_t)kSplitBufX * kSplitSlotsX) * 16;  // 160 KB
+  static_assert(lds_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+  auto kern = hash_split_kernel<DT>;
+  static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
+  if (!raised.load(std::memory_order_acquire)) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    raised.store(true, std::memory_order_release);
+  }
+  const dim3 grid((uint32_t)((T + kSplitTokens - 1) / kSplitTokens)), block(kSplitWaves * 64);
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg);
+  return hipGetLastError();
+}
+
 template <typename DT, int MT, int NTK, int XDEPTH, int WAVES, int OCC, bool ALIGNED8, bool KTAIL>
 hipError_t launch_one(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
                       hipStream_t stream) {
@@ -328,6 +555,10 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
   // staging of R dominates, and 8 waves sharing one staged copy beat two 4-wave workgroups with one each.
   // OCC: waves per SIMD the register budget is cut for - while one wave waits at a chunk barrier another
   // issues MFMAs.
+  // Widest groups on large inputs: the 4 x 2 tiling with both operands staged through LDS (see hash_split_kernel).
+  // Measured at T = 65536, d = 1024, 256 rows: 42 us against 45 us with tokens coming from HBM, 47 us against
+  // 43 us when the tokens are still in the last-level cache.
+  if (mt >= 7 && fast && T >= 256 * 256) return launch_split<DT>(x, R, bucket, T, row_pieces, L, r, hpg, stream);
   if (mt >= 6) {
     const bool wide = T >= 256 * 256;
     if (mt == 6) return wide ? LSHMOE_HASH(6, 1, 2, 8, 1) : LSHMOE_HASH(6, 1, 2, 4, 2);

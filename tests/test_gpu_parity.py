@@ -198,6 +198,45 @@ def test_exact_ties_on_the_fast_hash_instance(H, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,r", [(4, 64), (2, 256), (7, 32)])
+def test_hash_widest_groups_on_large_inputs(H, dtype, L, r):
+    # 193..256 rows of R per pass and T >= 65536 select the kernel that splits the rows of R between two waves
+    # and joins the halves at the end: random tokens plus exact +-ties inside a lane, across lane halves, across
+    # tiles and across the two row halves, at the start and in the ragged tail; r = 256 puts ONE hash on both
+    # halves, L = 7 with r = 32 leaves the last 32 staged rows unused
+    import oracle
+    T = 65536 + 77
+    d = 256 if dtype == "bf16" else 128
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    rot = rng.standard_normal((L, r, d)).astype(np.float32) * 0.05
+    cols = min(r, d)
+    for l in range(L):                        # rows 0..cols-1 of every hash pick out one coordinate each
+        rot[l, :cols, :] = 0.0
+        rot[l, np.arange(cols), (np.arange(cols) + 8 * l) % d] = 1.0
+    special = [0, 1, 2, 3, 4, 5, 31, 32, 255, 256, 65535, 65536, T - 2, T - 1]
+    pairs = [(1, 2), (2, 5), (3, 40), (10, min(cols, 200) - 1), (0, cols - 1), (7, 8), (33, 97 % cols)]
+    for j, t in enumerate(special):
+        x[t, :] = 0.0
+        a, b = pairs[j % len(pairs)]
+        sgn = 1.0 if j % 2 else -1.0
+        x[t, a % d] = sgn * 4.0               # hash 0 sees rows a and b tie at magnitude 4 with opposite signs
+        x[t, b % d] = -sgn * 4.0
+    x[special[5], :] = 0.0                    # and one all-zero token
+    tokens, rots = synth.f32_to_storage(x, dtype), synth.f32_to_storage(rot, dtype)
+    xt, rt = H.to_device(tokens, dtype), H.to_device(rots, dtype)
+    bt = torch.full((T + 8,), -1, dtype=torch.int64, device="cuda")
+    H.lsh.lshmoe_hash(xt, rt, bt[:T])
+    torch.cuda.synchronize()
+    got = bt.cpu().numpy()
+    assert np.all(got[T:] == -1), "ids past T must stay untouched"
+    bucket = got[:T].view(np.uint64)
+    H.check_hash(bucket, tokens, rots, dtype)
+    ref, _, margin, _ = oracle.hash_ref(tokens, rots, dtype)
+    assert np.array_equal(bucket[special], ref[special]), "exact ties resolve to the lowest row, as in the oracle"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_no_residual_flag_and_without_seg_offsets(H, dtype):
     tokens, rot, expert = _rand_inputs(9, 900, 32, 2, 6, 2, 8, dtype, centers=30)
     H.run_and_check(tokens, rot, expert, 6, dtype, _scale_fn, flags=H.lsh.LSHMOE_FLAG_NO_RESIDUAL)
