@@ -413,8 +413,7 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void hash_split_kernel(
 
     // Signed arg-max per hash over the rows this wave holds (tiles mh*4 .. mh*4+3), then joined with the other
     // half of the rows through LDS.  Same two-pass integer scheme as hash_kernel's aligned epilogue.
-    uint2* ex = reinterpret_cast<uint2*>(lds);   // [kSplitTokens][nh]: {magnitude bits, row | sign << 31} of the upper half
-    uint32_t best_s[NTW], code_s[NTW];
+    uint2* ex = reinterpret_cast<uint2*>(lds);   // [2 halves][kSplitTokens][nh]: {magnitude bits, row | sign << 31}
     for (int lh = 0; lh < nh; ++lh) {
       const int lo = lh * r;
 #pragma unroll
@@ -472,18 +471,22 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void hash_split_kernel(
           bi = obi;
           neg = oneg != 0;
         }
-        best_s[u] = best;
-        code_s[u] = (uint32_t)bi | (neg ? 0x80000000u : 0u);
-        if (mh == 1 && h == 0) ex[(g * NTW * 32 + u * 32 + n) * nh + lh] = make_uint2(best, code_s[u]);
+        if (h == 0)
+          ex[((mh * kSplitTokens) + g * NTW * 32 + u * 32 + n) * nh + lh] =
+              make_uint2(best, (uint32_t)bi | (neg ? 0x80000000u : 0u));
       }
-      __syncthreads();                       // the upper halves are in LDS (every wave reaches this: nh is uniform)
-      if (mh == 0) {
+    }
+    __syncthreads();                         // both halves of every token are in LDS
+    if (mh == 0 && h == 0) {
 #pragma unroll
-        for (int u = 0; u < NTW; ++u) {
-          const uint2 o = ex[(g * NTW * 32 + u * 32 + n) * nh + lh];
-          uint32_t code = code_s[u];
+      for (int u = 0; u < NTW; ++u) {
+        const int tok = g * NTW * 32 + u * 32 + n;
+        for (int lh = 0; lh < nh; ++lh) {
+          const uint2 lo_half = ex[tok * nh + lh], hi_half = ex[(kSplitTokens + tok) * nh + lh];
+          uint32_t code = lo_half.y;
           // rows of the upper half are higher, so on equal magnitude the lower half wins unless it holds no row
-          if (o.x > best_s[u] || (o.x == best_s[u] && (o.y & 0x7fffffffu) < (code & 0x7fffffffu))) code = o.y;
+          if (hi_half.x > lo_half.x || (hi_half.x == lo_half.x && (hi_half.y & 0x7fffffffu) < (code & 0x7fffffffu)))
+            code = hi_half.y;
           b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)((code & 0x7fffffffu) + ((code >> 31) ? (uint32_t)r : 0u));
         }
       }
