@@ -289,15 +289,26 @@ __global__ __launch_bounds__(WAVES * 64, OCC) void hash_kernel(const char* __res
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Variant for the widest hash groups (193..256 rows of R) on large inputs.  With eight 32-row tiles and one
-// 32-token tile per wave, every MFMA needs a fresh A fragment from LDS, which is exactly the LDS read peak
-// (1 KB per 32-cycle MFMA and SIMD), and the direct token loads (32 bytes of 32 different rows per
-// instruction) load the address path.  Here a wave keeps 4 row tiles x 2 token tiles instead: 8 waves = 4
-// token groups of 64 x 2 halves of the rows.  Per MFMA step a wave reads 4 A and 2 B fragments for 8 MFMAs
-// (0.75 KB per MFMA), and the tokens are staged through LDS like R, with full-line coalesced global loads
-// that write LDS directly: the two waves that share a token group read them from LDS, not twice from memory.  The two row halves of
-// a token are joined at the end through LDS.
+// Streaming variant: BOTH operands are staged through LDS by direct global->LDS loads, several chunks ahead.
+//
+// Why.  In hash_kernel the tokens go straight into registers: 32 bytes of 32 different rows per load
+// instruction, which loads the address path, and with eight 32-row tiles and one 32-token tile per wave
+// every MFMA needs a fresh A fragment from LDS, which is exactly the LDS read peak (1 KB per 32-cycle MFMA
+// and SIMD).  Here the token rows are fetched as whole 128-byte lines (8 lanes per row), need no staging
+// registers and no LDS write instructions, and a wave keeps MTW x NTW tiles, so that with NTW = 2 a wave
+// reads MTW + 2 fragments for 2*MTW MFMAs.
+//
+// Shape.  A workgroup has GROUPS token groups of NTW*32 tokens and, for the widest hash groups, HALVES = 2
+// waves per token group that each hold half of the rows of R (two waves sharing a token group read the
+// tokens from LDS, not twice from memory); their results are joined at the end through LDS.
+//
+// Staging.  Chunk c (128 bytes of every row) of R sits in slot c % (DR + 1) of a ring, of the tokens in slot
+// c % (DX + 1); iteration c issues the loads of R chunk c + DR and token chunk c + DX (R from L2, the tokens
+// from HBM, hence the longer distance).  The loads of a wave complete in issue order, so "chunk c + 1 has
+// landed" is a wait until at most kAllowed of the wave's loads are in flight, followed by the barrier that
+// closes the iteration.
 // Requires: r a multiple of 8, rows a whole number of 128-byte chunks.
+//
 // 16 bytes per lane straight from global memory into LDS: lane l's piece lands at dst + l (dst is wave-uniform).
 // Written as inline assembly on purpose: for the compiler's own builtin the wait-count pass holds every later
 // LDS read until the load has landed, which would serialise the staging with the MFMA loop.  The caller
@@ -307,62 +318,76 @@ __device__ __forceinline__ void load16_to_lds(const char* src, uint4* dst) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
 }
 
-constexpr int kSplitWaves = 8, kSplitRows = 256, kSplitTokens = 256;
-constexpr int kSplitSlotsR = kSplitRows * kPieces, kSplitSlotsX = kSplitTokens * kPieces;  // 16-byte slots per buffer (32 KB each)
-constexpr int kSplitBufR = 2, kSplitBufX = 3;  // R comes from L2, one chunk ahead; the tokens from HBM, two chunks ahead
+// s_waitcnt until at most n vector-memory operations of the wave are in flight (LDS and scalar counters untouched).
+template <int N> __device__ __forceinline__ void wait_vm_at_most() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
 
-template <typename DT>
-__global__ __launch_bounds__(kSplitWaves * 64, 1) void hash_split_kernel(
+template <int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX> struct StreamShape {
+  static constexpr int kWaves = GROUPS * HALVES;
+  static constexpr int kRows = MTW * HALVES * 32;    // rows of R staged per chunk
+  static constexpr int kTokens = GROUPS * NTW * 32;  // tokens of a workgroup
+  static constexpr int kSlotsR = kRows * kPieces, kSlotsX = kTokens * kPieces;  // 16-byte slots per ring slot
+  static constexpr size_t kLdsBytes = ((size_t)(DR + 1) * kSlotsR + (size_t)(DX + 1) * kSlotsX) * 16;
+};
+
+template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX>
+__global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
     const char* __restrict__ tokens, const char* __restrict__ rot, uint64_t* __restrict__ bucket, uint32_t T,
     int row_pieces, int L, int r, int hpg) {
-  constexpr int MTW = 4, NTW = 2;            // tiles per wave: rows x tokens
-  constexpr int TH = kSplitWaves * 64;
-  constexpr int LS = kSplitRows * kPieces / TH;  // staging loads per thread, chunk and operand: 4
-  extern __shared__ uint4 lds[];             // R chunks [kSplitBufR][kSplitSlotsR], then token chunks [kSplitBufX][kSplitSlotsX]
+  using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
+  constexpr int WAVES = S::kWaves, TH = WAVES * 64;
+  constexpr int LR = S::kRows / 8 / WAVES, LX = S::kTokens / 8 / WAVES;  // direct loads per wave and chunk
+  static_assert(S::kRows % (8 * WAVES) == 0 && S::kTokens % (8 * WAVES) == 0, "whole 8-row loads per wave");
+  static_assert(DX == DR + 1 && DR >= 1, "the wait below assumes the tokens run one chunk further ahead than R");
+  constexpr int kAllowed = (DR - 1) * (LR + LX) + LX;  // loads issued after those of chunk c + 1, at the end of iteration c
+  extern __shared__ uint4 lds[];             // R ring [DR + 1][kSlotsR], then token ring [DX + 1][kSlotsX]
   const int tid = threadIdx.x;
   __builtin_assume(tid >= 0 && tid < TH);
   const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
-  const int g = wave >> 1, mh = wave & 1;    // token group, half of the rows
+  const int g = wave / HALVES, mh = wave % HALVES;   // token group, half of the rows
   const uint32_t row_bytes = (uint32_t)row_pieces * 16u;
   const int nchunks = row_pieces / kPieces;
-  const uint32_t tok_blk = blockIdx.x * (uint32_t)kSplitTokens;
+  const uint32_t tok_blk = blockIdx.x * (uint32_t)S::kTokens;
   const char* x_blk = tokens + (size_t)tok_blk * row_bytes;
 
-  // Staging uses the direct global->LDS load: a wave's instruction drops 64 x 16 bytes at consecutive LDS
-  // slots (lane l at slot base + l), i.e. 8 rows x 8 pieces; the swizzle is applied by choosing which piece of
-  // the row a lane fetches.  No staging registers and no LDS write instructions.
+  // a wave's load instruction covers 8 rows x 8 pieces (lane l at slot base + l); the swizzle is applied by
+  // choosing which piece of the row a lane fetches
   const int wv = __builtin_amdgcn_readfirstlane(wave);
-  const int sub = lane >> 3, pc = (lane & 7) ^ sub;   // row inside the 8-row group, logical piece this lane fetches
-  uint32_t off_x[LS];
+  const int sub = lane >> 3, pc = (lane & 7) ^ sub;  // row inside the 8-row group, logical piece this lane fetches
+  uint32_t off_x[LX];
 #pragma unroll
-  for (int i = 0; i < LS; ++i)               // token rows past the end re-read the last token
-    off_x[i] = (min(tok_blk + (uint32_t)(32 * wv + 8 * i + sub), T - 1) - tok_blk) * row_bytes + pc * 16;
+  for (int i = 0; i < LX; ++i)               // token rows past the end re-read the last token
+    off_x[i] = (min(tok_blk + (uint32_t)(8 * (wv * LX + i) + sub), T - 1) - tok_blk) * row_bytes + pc * 16;
   int fslot[kSteps];
 #pragma unroll
   for (int s = 0; s < kSteps; ++s) fslot[s] = n * kPieces + swizzle(n, 2 * s + h);
-  const int a_tile0 = mh * MTW * 32 * kPieces;   // first slot of this wave's row tiles inside an R buffer
-  const int b_tile0 = g * NTW * 32 * kPieces;    // ... and of its token tiles inside a token buffer
-  uint4* const lds_x = lds + kSplitBufR * kSplitSlotsR;
+  const int a_tile0 = mh * MTW * 32 * kPieces;   // first slot of this wave's row tiles inside an R ring slot
+  const int b_tile0 = g * NTW * 32 * kPieces;    // ... and of its token tiles inside a token ring slot
+  uint4* const lds_x = lds + (DR + 1) * S::kSlotsR;
 
-  uint64_t b[NTW] = {0, 0};
+  uint64_t b[NTW];
+#pragma unroll
+  for (int u = 0; u < NTW; ++u) b[u] = 0;
   for (int l0 = 0; l0 < L; l0 += hpg) {
     const int nh = min(hpg, L - l0);
     const int rows = nh * r;                 // valid rows of R in this group; staging rows past them repeat the last
     const char* rot_group = rot + (size_t)l0 * r * row_bytes;
-    uint32_t off_a[LS];
+    uint32_t off_a[LR];
 #pragma unroll
-    for (int i = 0; i < LS; ++i) off_a[i] = (uint32_t)min(32 * wv + 8 * i + sub, rows - 1) * row_bytes + pc * 16;
+    for (int i = 0; i < LR; ++i) off_a[i] = (uint32_t)min(8 * (wv * LR + i) + sub, rows - 1) * row_bytes + pc * 16;
 
     auto stage_r = [&](int chunk) {
-      uint4* dst = lds + (chunk % kSplitBufR) * kSplitSlotsR + (32 * wv) * kPieces;
+      uint4* dst = lds + (chunk % (DR + 1)) * S::kSlotsR + (8 * wv * LR) * kPieces;
 #pragma unroll
-      for (int i = 0; i < LS; ++i) load16_to_lds(rot_group + (size_t)chunk * (kPieces * 16) + off_a[i], dst + 8 * i * kPieces);
+      for (int i = 0; i < LR; ++i) load16_to_lds(rot_group + (size_t)chunk * (kPieces * 16) + off_a[i], dst + 8 * i * kPieces);
     };
     auto stage_x = [&](int chunk) {
-      uint4* dst = lds_x + (chunk % kSplitBufX) * kSplitSlotsX + (32 * wv) * kPieces;
+      uint4* dst = lds_x + (chunk % (DX + 1)) * S::kSlotsX + (8 * wv * LX) * kPieces;
 #pragma unroll
-      for (int i = 0; i < LS; ++i) load16_to_lds(x_blk + (size_t)chunk * (kPieces * 16) + off_x[i], dst + 8 * i * kPieces);
+      for (int i = 0; i < LX; ++i) load16_to_lds(x_blk + (size_t)chunk * (kPieces * 16) + off_x[i], dst + 8 * i * kPieces);
     };
 
     floatx16 acc[MTW][NTW];
@@ -374,18 +399,20 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void hash_split_kernel(
         for (int j = 0; j < 16; ++j) acc[t][u][j] = 0.0f;
 
     __syncthreads();                         // previous group's readers are done with LDS
-    stage_r(0);
-    stage_x(0);
-    if (nchunks > 1) stage_x(1);
-    // direct loads complete in issue order: all but the newest LS (the second token chunk) have landed
-    if (nchunks > 1) __builtin_amdgcn_s_waitcnt(0x0f70 | LS); else __builtin_amdgcn_s_waitcnt(0x0f70);
+    // chunks 0 .. DR-1 of R and 0 .. DX-1 of the tokens, in the order the loop would have issued them
+#pragma unroll
+    for (int j = 0; j < DX; ++j) {
+      if (j < DR && j < nchunks) stage_r(j);
+      if (j < nchunks) stage_x(j);
+    }
+    if (nchunks > DX) wait_vm_at_most<kAllowed>(); else wait_vm_at_most<0>();  // chunk 0 has landed
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
-      // buffers written now were last read in chunk c - 1, whose closing barrier every wave has passed
-      if (c + 1 < nchunks) stage_r(c + 1);
-      if (c + 2 < nchunks) stage_x(c + 2);
-      const uint4* bufa = lds + (c % kSplitBufR) * kSplitSlotsR;
-      const uint4* bufb = lds_x + (c % kSplitBufX) * kSplitSlotsX;
+      // ring slots written now were last read in chunk c - 1, whose closing barrier every wave has passed
+      if (c + DR < nchunks) stage_r(c + DR);
+      if (c + DX < nchunks) stage_x(c + DX);
+      const uint4* bufa = lds + (c % (DR + 1)) * S::kSlotsR;
+      const uint4* bufb = lds_x + (c % (DX + 1)) * S::kSlotsX;
       uint4 fa[2][MTW], fb[2][NTW];          // fragments of the step in flight and of the next one
 #pragma unroll
       for (int t = 0; t < MTW; ++t) fa[0][t] = bufa[a_tile0 + t * 32 * kPieces + fslot[0]];
@@ -406,14 +433,14 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void hash_split_kernel(
           for (int u = 0; u < NTW; ++u) Mma<DT>::run(fa[s & 1][t], fb[s & 1][u], acc[t][u]);
         __builtin_amdgcn_sched_barrier(0);
       }
-      // chunk c + 1 must have landed: everything but the LS newest loads (token chunk c + 2, when there is one)
-      if (c + 2 < nchunks) __builtin_amdgcn_s_waitcnt(0x0f70 | LS); else __builtin_amdgcn_s_waitcnt(0x0f70);
+      // chunk c + 1 must have landed: everything but the loads issued after it (none of them near the end)
+      if (c + DX < nchunks) wait_vm_at_most<kAllowed>(); else wait_vm_at_most<0>();
       __syncthreads();
     }
 
-    // Signed arg-max per hash over the rows this wave holds (tiles mh*4 .. mh*4+3), then joined with the other
-    // half of the rows through LDS.  Same two-pass integer scheme as hash_kernel's aligned epilogue.
-    uint2* ex = reinterpret_cast<uint2*>(lds);   // [2 halves][kSplitTokens][nh]: {magnitude bits, row | sign << 31}
+    // Signed arg-max per hash over the rows this wave holds (tiles mh*MTW .. mh*MTW + MTW-1).  Same two-pass
+    // integer scheme as hash_kernel's aligned epilogue.  With two halves the results are joined through LDS.
+    uint2* ex = reinterpret_cast<uint2*>(lds);   // [HALVES][kTokens][nh]: {magnitude bits, row | sign << 31}
     for (int lh = 0; lh < nh; ++lh) {
       const int lo = lh * r;
 #pragma unroll
@@ -471,23 +498,28 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void hash_split_kernel(
           bi = obi;
           neg = oneg != 0;
         }
-        if (h == 0)
-          ex[((mh * kSplitTokens) + g * NTW * 32 + u * 32 + n) * nh + lh] =
+        if (HALVES == 1) {
+          b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)(bi + (neg ? r : 0));
+        } else if (h == 0) {
+          ex[((mh * S::kTokens) + g * NTW * 32 + u * 32 + n) * nh + lh] =
               make_uint2(best, (uint32_t)bi | (neg ? 0x80000000u : 0u));
+        }
       }
     }
-    __syncthreads();                         // both halves of every token are in LDS
-    if (mh == 0 && h == 0) {
+    if (HALVES == 2) {
+      __syncthreads();                       // both halves of every token are in LDS
+      if (mh == 0 && h == 0) {
 #pragma unroll
-      for (int u = 0; u < NTW; ++u) {
-        const int tok = g * NTW * 32 + u * 32 + n;
-        for (int lh = 0; lh < nh; ++lh) {
-          const uint2 lo_half = ex[tok * nh + lh], hi_half = ex[(kSplitTokens + tok) * nh + lh];
-          uint32_t code = lo_half.y;
-          // rows of the upper half are higher, so on equal magnitude the lower half wins unless it holds no row
-          if (hi_half.x > lo_half.x || (hi_half.x == lo_half.x && (hi_half.y & 0x7fffffffu) < (code & 0x7fffffffu)))
-            code = hi_half.y;
-          b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)((code & 0x7fffffffu) + ((code >> 31) ? (uint32_t)r : 0u));
+        for (int u = 0; u < NTW; ++u) {
+          const int tok = g * NTW * 32 + u * 32 + n;
+          for (int lh = 0; lh < nh; ++lh) {
+            const uint2 lo_half = ex[tok * nh + lh], hi_half = ex[(S::kTokens + tok) * nh + lh];
+            uint32_t code = lo_half.y;
+            // rows of the upper half are higher, so on equal magnitude the lower half wins unless it holds no row
+            if (hi_half.x > lo_half.x || (hi_half.x == lo_half.x && (hi_half.y & 0x7fffffffu) < (code & 0x7fffffffu)))
+              code = hi_half.y;
+            b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)((code & 0x7fffffffu) + ((code >> 31) ? (uint32_t)r : 0u));
+          }
         }
       }
     }
@@ -501,20 +533,20 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void hash_split_kernel(
   }
 }
 
-template <typename DT>
-hipError_t launch_split(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
-                        hipStream_t stream) {
-  constexpr size_t lds_bytes = ((size_t)kSplitBufR * kSplitSlotsR + (size_t)kSplitBufX * kSplitSlotsX) * 16;  // 160 KB
-  static_assert(lds_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
-  auto kern = hash_split_kernel<DT>;
+template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX>
+hipError_t launch_stream(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
+                         hipStream_t stream) {
+  using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
+  static_assert(S::kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+  auto kern = hash_stream_kernel<DT, MTW, NTW, GROUPS, HALVES, DR, DX>;
   static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
   if (!raised.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes);
     if (e != hipSuccess) return e;
     raised.store(true, std::memory_order_release);
   }
-  const dim3 grid((uint32_t)((T + kSplitTokens - 1) / kSplitTokens)), block(kSplitWaves * 64);
-  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg);
+  const dim3 grid((uint32_t)((T + S::kTokens - 1) / S::kTokens)), block(S::kWaves * 64);
+  hipLaunchKernelGGL(kern, grid, block, S::kLdsBytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg);
   return hipGetLastError();
 }
 
@@ -558,10 +590,26 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
   // staging of R dominates, and 8 waves sharing one staged copy beat two 4-wave workgroups with one each.
   // OCC: waves per SIMD the register budget is cut for - while one wave waits at a chunk barrier another
   // issues MFMAs.
-  // Widest groups on large inputs: the 4 x 2 tiling with both operands staged through LDS (see hash_split_kernel).
+  // Widest groups on large inputs: the 4 x 2 tiling with the rows of R split between two waves (see hash_stream_kernel).
   // Measured at T = 65536, d = 1024, 256 rows: 42 us against 45 us with tokens coming from HBM, 47 us against
   // 43 us when the tokens are still in the last-level cache.
-  if (mt >= 7 && fast && T >= 256 * 256) return launch_split<DT>(x, R, bucket, T, row_pieces, L, r, hpg, stream);
+  if (mt >= 7 && fast && T >= 256 * 256)
+    return launch_stream<DT, 4, 2, 4, 2, 1, 2>(x, R, bucket, T, row_pieces, L, r, hpg, stream);
+  // Few rows of R (mt <= 4): the kernel is bound by streaming the tokens.  From about 8k tokens on the streaming
+  // kernel wins (measured per call: GPT shape 23.7 -> 18.9 us, Swin 12.7 -> 10.6, RoBERTa 13.1 -> 10.7): 128-token
+  // workgroups of four waves with the tokens four chunks ahead once there are enough tokens for ~200 of them,
+  // else 64-token workgroups of two waves three chunks ahead.
+  if (fast && mt <= 4 && T >= 8192) {
+    const bool big = T >= 24576;
+#define LSHMOE_STREAM(MT) \
+    (big ? launch_stream<DT, MT, 1, 4, 1, 3, 4>(x, R, bucket, T, row_pieces, L, r, hpg, stream) \
+         : launch_stream<DT, MT, 1, 2, 1, 2, 3>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
+    if (mt <= 1) return LSHMOE_STREAM(1);
+    if (mt == 2) return LSHMOE_STREAM(2);
+    if (mt == 3) return LSHMOE_STREAM(3);
+    return LSHMOE_STREAM(4);
+#undef LSHMOE_STREAM
+  }
   if (mt >= 6) {
     const bool wide = T >= 256 * 256;
     if (mt == 6) return wide ? LSHMOE_HASH(6, 1, 2, 8, 1) : LSHMOE_HASH(6, 1, 2, 4, 2);

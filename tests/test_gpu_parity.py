@@ -198,14 +198,16 @@ def test_exact_ties_on_the_fast_hash_instance(H, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("L,r", [(4, 64), (2, 256), (7, 32)])
-def test_hash_widest_groups_on_large_inputs(H, dtype, L, r):
-    # 193..256 rows of R per pass and T >= 65536 select the kernel that splits the rows of R between two waves
-    # and joins the halves at the end: random tokens plus exact +-ties inside a lane, across lane halves, across
-    # tiles and across the two row halves, at the start and in the ragged tail; r = 256 puts ONE hash on both
-    # halves, L = 7 with r = 32 leaves the last 32 staged rows unused
+@pytest.mark.parametrize("T,L,r", [(65536 + 77, 4, 64), (65536 + 77, 2, 256), (65536 + 77, 7, 32),
+                                   (32768 + 77, 3, 32), (24576 + 3, 1, 16), (16384 + 5, 2, 32), (8192 + 1, 2, 64)])
+def test_hash_streaming_instances(H, dtype, T, L, r):
+    # Large inputs with rows of whole 128-byte chunks take the kernels that stage both operands through LDS:
+    # 193..256 rows of R per pass and T >= 65536 the one that splits the rows of R between two waves and joins the
+    # halves at the end (r = 256 puts ONE hash on both halves, L = 7 with r = 32 leaves the last 32 staged rows
+    # unused); up to 128 rows the 128-token (T >= 24576) or 64-token workgroups.  Random tokens plus exact +-ties
+    # inside a lane, across lane halves, across tiles and across the two row halves, at the start and in the
+    # ragged tail.
     import oracle
-    T = 65536 + 77
     d = 256 if dtype == "bf16" else 128
     rng = np.random.default_rng(41)
     x = rng.standard_normal((T, d)).astype(np.float32)
@@ -214,8 +216,8 @@ def test_hash_widest_groups_on_large_inputs(H, dtype, L, r):
     for l in range(L):                        # rows 0..cols-1 of every hash pick out one coordinate each
         rot[l, :cols, :] = 0.0
         rot[l, np.arange(cols), (np.arange(cols) + 8 * l) % d] = 1.0
-    special = [0, 1, 2, 3, 4, 5, 31, 32, 255, 256, 65535, 65536, T - 2, T - 1]
-    pairs = [(1, 2), (2, 5), (3, 40), (10, min(cols, 200) - 1), (0, cols - 1), (7, 8), (33, 97 % cols)]
+    special = [0, 1, 2, 3, 4, 5, 31, 32, 255, 256, T - 79, T - 78, T - 2, T - 1]
+    pairs = [(1, 2), (2, 5), (3, 40 % cols), (10, min(cols, 200) - 1), (0, cols - 1), (7, 8), (33 % cols, 97 % cols)]
     for j, t in enumerate(special):
         x[t, :] = 0.0
         a, b = pairs[j % len(pairs)]
