@@ -22,8 +22,9 @@ template <int LPR> __device__ __forceinline__ int32_t uniform(int32_t v) {
   return LPR == 64 ? __builtin_amdgcn_readfirstlane(v) : v;  // a whole wave shares the value: keep it scalar
 }
 
-// Compensated sum of the token rows at sorted positions [a, b) (wave-wide, every lane takes pieces lane and
-// lane + 64 of each column group), written as binary32 to out_row.
+// Compensated sum of the token rows at sorted positions [a, b) (wave-wide, lanes stride over the 16-byte
+// pieces of the row), written as binary32 to out_row.  Kept small in registers on purpose: the kernel's
+// occupancy is set by its largest path, and this one runs for long clusters only.
 template <typename DT>
 __device__ __forceinline__ void window_sum(const char* __restrict__ tokens, const int32_t* __restrict__ perm,
                                            int32_t a, int32_t b, uint32_t k, uint32_t cpr, size_t row_bytes,
@@ -31,50 +32,35 @@ __device__ __forceinline__ void window_sum(const char* __restrict__ tokens, cons
   constexpr int E = Piece<DT>::kElems;
   constexpr int kRows = 8;
   const uint32_t lane = threadIdx.x & 63;
-  for (uint32_t c0 = 0; c0 < cpr; c0 += 128) {
-    const uint32_t c[2] = {c0 + lane, c0 + 64 + lane};
-    float acc[2][E], comp[2][E];
+  for (uint32_t c = lane; c < cpr; c += 64) {
+    float acc[E], comp[E];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int i = 0; i < E; ++i) acc[h][i] = comp[h][i] = 0.0f;
+    for (int i = 0; i < E; ++i) acc[i] = comp[i] = 0.0f;
     for (int32_t p = a; p < b; p += kRows) {
-      uint4 q[kRows][2];
+      uint4 q[kRows];
 #pragma unroll
       for (int u = 0; u < kRows; ++u) {
         const int32_t pp = min(p + u, b - 1);  // the surplus rows of the last round are loaded and not added
-        const char* row = tokens + (size_t)((uint32_t)__builtin_amdgcn_readfirstlane(perm[pp]) / k) * row_bytes;
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-          if (c[h] < cpr) q[u][h] = load16(row + c[h] * 16);
+        q[u] = load16(tokens + (size_t)((uint32_t)__builtin_amdgcn_readfirstlane(perm[pp]) / k) * row_bytes + c * 16);
       }
 #pragma unroll
       for (int u = 0; u < kRows; ++u) {
         if (p + u < b) {
+          float x[E];
+          Piece<DT>::widen(q[u], x);
 #pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            if (c[h] < cpr) {
-              float x[E];
-              Piece<DT>::widen(q[u][h], x);
-#pragma unroll
-              for (int i = 0; i < E; ++i) {
-                const float y = x[i] - comp[h][i];
-                const float t = acc[h][i] + y;
-                comp[h][i] = (t - acc[h][i]) - y;
-                acc[h][i] = t;
-              }
-            }
+          for (int i = 0; i < E; ++i) {
+            const float y = x[i] - comp[i];
+            const float t = acc[i] + y;
+            comp[i] = (t - acc[i]) - y;
+            acc[i] = t;
           }
         }
       }
     }
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-      if (c[h] < cpr) {
-#pragma unroll
-        for (int i = 0; i < E; i += 4)
-          *(float4*)(out_row + (size_t)c[h] * E + i) = make_float4(acc[h][i], acc[h][i + 1], acc[h][i + 2], acc[h][i + 3]);
-      }
+    for (int i = 0; i < E; i += 4)
+      *(float4*)(out_row + (size_t)c * E + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
   }
 }
 
@@ -106,7 +92,7 @@ __device__ __forceinline__ void long_cluster_window(
   const uint32_t nwin = m1 - m0 + 1;
   const float fn = (float)(hi - lo);
   char* dst = centroids + (size_t)s * row_bytes;
-  constexpr int kRows = 8;
+  constexpr int kRows = 4;
   for (uint32_t c = lane; c < cpr; c += 64) {
     float acc[E], comp[E];
 #pragma unroll
