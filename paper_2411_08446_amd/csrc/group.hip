@@ -367,7 +367,8 @@ __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(
     const uint64_t* __restrict__ key, const int32_t* __restrict__ perm, uint32_t N, uint32_t E, int bbits,
     const uint32_t* __restrict__ blocksum, int32_t* __restrict__ seg_offsets, int32_t* __restrict__ seg_expert,
     int32_t* __restrict__ expert_offsets, int32_t* __restrict__ seg_of, int32_t* __restrict__ num_segments,
-    uint32_t* __restrict__ window_counters = nullptr) {
+    uint32_t* __restrict__ window_counters = nullptr, const uint4* __restrict__ chunk_heads = nullptr,
+    const uint32_t* __restrict__ chunk_count = nullptr) {
   __shared__ uint32_t wave_sum[kSegThreads / kWave];
   constexpr uint32_t kCountersPerTile = 2 * kSegTile / kCentroidWindow;
   if (window_counters != nullptr && threadIdx.x < kCountersPerTile)  // when no seg_count_kernel ran to clear them
@@ -376,6 +377,14 @@ __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(
   if (SELF_PREFIX) {
     uint32_t part = 0;
     for (uint32_t t = threadIdx.x; t < blockIdx.x; t += kSegThreads) part += blocksum[t];
+    if (chunk_heads != nullptr) {
+      // heads of bins sorted as one chunk come per chunk: {first tile, heads in that tile and the next two}
+      const uint32_t nch = *chunk_count;
+      for (uint32_t c = threadIdx.x; c < nch; c += kSegThreads) {
+        const uint4 v = chunk_heads[c];
+        part += (v.x < blockIdx.x ? v.y : 0u) + (v.x + 1 < blockIdx.x ? v.z : 0u) + (v.x + 2 < blockIdx.x ? v.w : 0u);
+      }
+    }
     block_exclusive_scan(part, wave_sum, tiles_before);
   } else {
     tiles_before = blocksum[blockIdx.x];
@@ -604,16 +613,18 @@ struct BinSortArgs {
   int shift[8], width[8];     // their digits, least significant first
   int sub_shift;              // sub-bin of a key is (key >> sub_shift) & sub_mask
   uint32_t sub_mask;
-  uint32_t* tile_heads;       // [tiles of kSegTile positions]: cluster heads per tile, added to as bins are finished
+  uint32_t* tile_heads;       // [tiles of kSegTile positions]: cluster heads per tile of bins of several chunks (atomics)
+  uint4* chunk_heads;         // [chunks]: {first tile, heads in it, in the next, in the one after} of a bin of one chunk
 };
 
-// Adds the heads counted in LDS per numbering tile (the chunk's positions touch at most kChunkTiles of them) to
-// the global per-tile counts.  Every thread of the workgroup calls it.
+// Publishes the heads counted in LDS per numbering tile (a chunk's positions touch at most kChunkTiles of them)
+// as the chunk's own record: plain stores, no contention (hundreds of workgroups adding to a handful of per-tile
+// counters cost several microseconds on small inputs).  Every thread of the workgroup calls it.
 constexpr int kChunkTiles = kBinChunk / kSegTile + 1;
-__device__ __forceinline__ void flush_tile_heads(const uint32_t* tile_cnt, uint32_t first_tile, uint32_t* tile_heads) {
+static_assert(kChunkTiles == 3, "a chunk record holds three tile counts");
+__device__ __forceinline__ void publish_chunk_heads(const uint32_t* tile_cnt, uint32_t first_tile, uint4* record) {
   __syncthreads();
-  if (threadIdx.x < (uint32_t)kChunkTiles && tile_cnt[threadIdx.x] != 0)
-    atomicAdd(&tile_heads[first_tile + threadIdx.x], tile_cnt[threadIdx.x]);
+  if (threadIdx.x == 0) *record = make_uint4(first_tile, tile_cnt[0], tile_cnt[1], tile_cnt[2]);
 }
 
 constexpr int kBinFast = 1024;                     // up to here the sub-bin way is tried first
@@ -706,7 +717,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
           if (alone && !repeat) atomicAdd(&tile_cnt[((lo + rank) >> kSegTileBits) - (lo >> kSegTileBits)], 1u);
         }
       }
-      if (alone) flush_tile_heads(tile_cnt, lo >> kSegTileBits, a.tile_heads);
+      publish_chunk_heads(tile_cnt, lo >> kSegTileBits, a.chunk_heads + blockIdx.x);  // zeros unless alone
       return;
     }
     __syncthreads();  // the radix way below reuses cnt
@@ -786,7 +797,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
     out_idx[lo + i] = fidx[i];
     if (alone && (i == 0 || fkey[i - 1] != k)) atomicAdd(&tile_cnt[((lo + i) >> kSegTileBits) - (lo >> kSegTileBits)], 1u);
   }
-  if (alone) flush_tile_heads(tile_cnt, lo >> kSegTileBits, a.tile_heads);
+  publish_chunk_heads(tile_cnt, lo >> kSegTileBits, a.chunk_heads + blockIdx.x);  // zeros unless alone
 }
 
 // Merge of the sorted chunks of a bin that has several: the final place of a key is the bin's start plus
@@ -964,6 +975,8 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
   off = align256(off + ((size_t)kGroupBins + 3) * 4);
   p.off_chunktbl = off;
   off = align256(off + ((size_t)kGroupBins + p.sort_blocks) * 4);  // a chunk per non-empty bin and per kBinChunk keys
+  p.off_chunkheads = off;
+  off = align256(off + ((size_t)kGroupBins + p.sort_blocks) * 16);
   const size_t windows = 2 * (size_t)((p.N + kCentroidWindow - 1) / kCentroidWindow);
   p.off_partial = off;
   off = align256(off + windows * (size_t)d * 4);
@@ -1035,6 +1048,7 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     b.sub_shift = plan.top_shift - sub_bits;
     b.sub_mask = (1u << sub_bits) - 1u;
     b.tile_heads = blocksum;
+    b.chunk_heads = (uint4*)(ws + plan.off_chunkheads);
     static_assert(kBinChunk == kSortTile, "the chunk bound below counts sort tiles");
     const dim3 chunks((uint32_t)kGroupBins + nblk), threads(kBinThreads);
     hipLaunchKernelGGL(bin_sort_kernel, chunks, threads, kBinSortLds, stream, b);
@@ -1042,7 +1056,8 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     // the heads per numbering tile are known: number the clusters (the tile count is within kSelfPrefixMaxTiles here)
     hipLaunchKernelGGL(seg_write_kernel<true>, dim3(plan.seg_blocks), dim3(kSegThreads), 0, stream,
                        (const uint64_t*)keybuf[1], perm, N, (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert,
-                       expert_offsets, seg_of, num_segments, (uint32_t*)(ws + plan.off_counters));
+                       expert_offsets, seg_of, num_segments, (uint32_t*)(ws + plan.off_counters),
+                       (const uint4*)b.chunk_heads, (const uint32_t*)(bin_start + kGroupBins + 1));
     return hipGetLastError();
   }
   for (int p = 0; p < (plan.msd ? 0 : plan.passes); ++p) {

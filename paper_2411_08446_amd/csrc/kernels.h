@@ -35,7 +35,7 @@ struct GroupPlan {
   uint32_t sort_blocks;  // tiles of kSortTile assignments
   uint32_t seg_blocks;   // tiles of kSegTile sorted positions
   // byte offsets into the workspace
-  size_t off_key[2], off_idx[2], off_table, off_blocksum, off_binstart, off_chunktbl;
+  size_t off_key[2], off_idx[2], off_table, off_blocksum, off_binstart, off_chunktbl, off_chunkheads;
   size_t off_partial, off_counters;  // window sums and window counters of the centroid step
   size_t total_bytes;
 };
