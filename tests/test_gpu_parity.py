@@ -299,6 +299,65 @@ def test_backward_long_clusters(H, dtype):
     H.check_backward(run, T, d, 2, dtype, seed=38)
 
 
+def test_path_replays_from_a_graph(H):
+    # the calls only enqueue kernels on the caller's stream (no allocation, no host synchronisation, no memset
+    # nodes), so a step can be captured once and replayed: three replays on fresh inputs, with eager work and
+    # synchronisations in between, each compared bit for bit with the eager result on the same inputs
+    lsh = H.lsh
+    cfg = synth.config("gpt", T=6000, centers=400)
+    T, d, k, E, L, r, N = cfg.T, cfg.d, cfg.k, cfg.E, cfg.L, cfg.r, cfg.N
+    ws = [synth.generate(cfg, seed=100 + i) for i in range(3)]
+    x = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    rot = H.to_device(ws[0].rot, cfg.dtype)
+    expert = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    ec = torch.randn((N, d), device="cuda").to(torch.bfloat16)
+    bucket = torch.empty(T, dtype=torch.int64, device="cuda")
+    out = lsh.CompressOutputs.allocate(T, d, k, E, L, r, torch.bfloat16)
+    y = torch.empty((T, k, d), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        lsh.lshmoe_hash(x, rot, bucket)
+        lsh.lshmoe_compress(x, expert, bucket, E, L, r, out)
+        lsh.lshmoe_decompress(x, out.centroids, ec, out.seg_of, out.seg_offsets, k, y)
+
+    def load(w):
+        x.copy_(H.to_device(w.tokens, cfg.dtype))
+        expert.copy_(torch.from_numpy(w.expert).cuda())
+
+    load(ws[0])
+    step()                                   # warm-up outside the capture (sets kernel attributes)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for w in ws:
+        load(w)
+        step()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (bucket, out.perm, out.seg_of, out.seg_offsets, out.num_segments, out.expert_offsets, y)]
+        S = int(out.num_segments.item())
+        want_c = out.centroids[:S].clone()
+        for t in (bucket, out.perm, out.seg_of, out.seg_offsets, out.num_segments, out.expert_offsets):
+            t.fill_(-3)
+        y.zero_()
+        out.centroids.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (bucket, out.perm, out.seg_of, out.seg_offsets, out.num_segments, out.expert_offsets, y)
+        assert torch.equal(got[4], want[4])
+        for g, wnt, name in zip(got, want, ("bucket", "perm", "seg_of", "seg_offsets", "S", "expert_offsets", "y")):
+            if name == "seg_offsets":
+                assert torch.equal(g[:S + 1], wnt[:S + 1]), name
+            else:
+                assert torch.equal(g, wnt), name
+        assert torch.equal(out.centroids[:S], want_c)
+
+
 def test_deterministic_across_runs(H):
     cfg = synth.config("gpt", T=4000, centers=300)
     w = synth.generate(cfg)
