@@ -216,6 +216,20 @@ def main():
     result["supplementary_fused_combine"] = {
         "decompress_combine_ms": comb_ms, "algorithmic_bytes": comb_bytes,
         "achieved_gbs": comb_bytes / (comb_ms * 1e-3) / 1e9 if comb_ms else None}
+    # supplementary: the hash fused with the gate's projection of the tokens (logits [T, E])
+    if d * item % 512 == 0 and r % 8 == 0 and E <= 128:
+        gate_w = (torch.randn((E, d), device="cuda") * 0.05).to(tdt)
+        logits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+        evg = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(K, 50))]
+        for i, (e0, e1) in enumerate(evg):
+            e0.record()
+            lsh.lshmoe_hash_gate(xs[i % copies], rot, gate_w, bucket, logits)
+            e1.record()
+        torch.cuda.synchronize()
+        if len(evg) > 5:
+            result["supplementary_hash_gate"] = {
+                "hash_gate_ms": float(np.mean([e0.elapsed_time(e1) for e0, e1 in evg[5:]])), "hash_ms": float(hash_ms),
+                "one_pass_over_tokens": bool(L * r + E <= 128)}
     # supplementary: backward of the path (segment sums of dL/dY, then dL/dx), on random gradients
     gy = torch.randn((T, k, d), device="cuda").to(tdt)
     hc = torch.randn((N, d), device="cuda").to(tdt)

@@ -9,7 +9,8 @@
  *                      replace every cluster by its centroid        (Alg. 1, the two nested loops)
  *   lshmoe_decompress  give every token the expert output of its
  *                      centroid plus the token's residual           (Eq. 4, Eq. 5)
- *   lshmoe_decompress_combine   the same fused with the gate-weighted sum over a token's experts (Eq. 2)
+ *   lshmoe_hash_gate            lshmoe_hash that also returns the gate's projection of the tokens (Eq. 1)
+ *   lshmoe_decompress_combine   lshmoe_decompress fused with the gate-weighted sum over a token's experts (Eq. 2)
  *   lshmoe_decompress_backward, lshmoe_compress_backward   gradients through the two calls above
  *
  * Notation: T tokens of dimension d; every token is routed to k distinct
@@ -111,6 +112,25 @@ lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E,
 lshmoe_status lshmoe_hash(const void* tokens, const void* rot,
                           int64_t T, int32_t d, int32_t L, int32_t r, lshmoe_dtype dtype,
                           uint64_t* bucket, void* stream);
+
+/*
+ * lshmoe_hash fused with the linear part of a learned gate (the gating network G of Section 2.1, Eq. 1; the
+ * paper leaves its form open; routers "via learnable weighting" start from a projection of the token):
+ *     logits[t, e] = < gate_w[e, :], tokens[t, :] >,   accumulated in binary32,
+ * computed by the same kernel and from the same read of the tokens as the bucket ids whenever
+ * L*r + E <= 128 (otherwise the tokens are read a second time for the gate rows).  Choosing the top-k experts
+ * from the logits stays with the caller.
+ *
+ *   gate_w [E, d]  in   dtype
+ *   logits [T, E]  out  binary32
+ *   other arguments and the bucket ids exactly as for lshmoe_hash.
+ *
+ * Errors: as for lshmoe_hash; NULL gate_w or logits; E <= 0 (SHAPE); shapes the fused kernel does not take
+ * (UNSUPPORTED): r not a multiple of 8, d*sizeof(element) not a multiple of 512, E > 128.
+ */
+lshmoe_status lshmoe_hash_gate(const void* tokens, const void* rot, const void* gate_w,
+                               int64_t T, int32_t d, int32_t L, int32_t r, int32_t E, lshmoe_dtype dtype,
+                               uint64_t* bucket, float* logits, void* stream);
 
 /*
  * Cluster and average (Algorithm 1: dispatch by expert, split each expert's

@@ -111,6 +111,13 @@ def hash_ref(tokens: np.ndarray, rot: np.ndarray, dtype: str):
     return bucket, code, margin, runner
 
 
+def gate_logits_ref(tokens: np.ndarray, gate_w: np.ndarray, dtype: str) -> np.ndarray:
+    """Linear part of a learned gate (the gating network of Section 2.1, Eq. 1,
+    whose form the paper leaves open): logits[t, e] = <gate_w[e, :], x_t>,
+    in binary64, not rounded.  tokens [T, d], gate_w [E, d] in storage form."""
+    return widen(tokens, dtype) @ widen(gate_w, dtype).T
+
+
 def combine_codes(code: np.ndarray, r: int) -> np.ndarray:
     """Digits code[:, 0..L-1] (each in [0, 2r)) -> one base-2r number, digit 0
     most significant."""

@@ -22,7 +22,7 @@ LSHMOE_ERR_HIP = 5
 LSHMOE_F32 = 0
 LSHMOE_BF16 = 1
 LSHMOE_FLAG_NO_RESIDUAL = 1
-ABI_VERSION = 3   # of include/lshmoe.h as this binding declares it
+ABI_VERSION = 4   # of include/lshmoe.h as this binding declares it
 
 
 class LshmoeError(RuntimeError):
@@ -58,6 +58,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.lshmoe_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
     lib.lshmoe_hash.restype = ctypes.c_int
     lib.lshmoe_hash.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, vp, vp]
+    lib.lshmoe_hash_gate.restype = ctypes.c_int
+    lib.lshmoe_hash_gate.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, ctypes.c_int, vp, vp, vp]
     lib.lshmoe_compress.restype = ctypes.c_int
     lib.lshmoe_compress.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_int,
                                     vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -120,6 +122,19 @@ def lshmoe_hash(tokens: torch.Tensor, rot: torch.Tensor, bucket: torch.Tensor, s
         raise ValueError("shape/dtype mismatch between tokens, rot and bucket")
     _check(load_library().lshmoe_hash(_ptr(tokens), _ptr(rot), T, d, L, r, _dtype_code(tokens),
                                       _ptr(bucket, torch.int64), _stream(stream)))
+
+
+def lshmoe_hash_gate(tokens: torch.Tensor, rot: torch.Tensor, gate_w: torch.Tensor, bucket: torch.Tensor,
+                     logits: torch.Tensor, stream=None) -> None:
+    """As lshmoe_hash, and logits [T, E] (float32) = tokens @ gate_w.T from the same pass over the tokens."""
+    T, d = tokens.shape
+    L, r, d2 = rot.shape
+    E = gate_w.shape[0]
+    if d2 != d or gate_w.shape[1] != d or rot.dtype != tokens.dtype or gate_w.dtype != tokens.dtype \
+            or bucket.numel() != T or logits.shape != (T, E):
+        raise ValueError("shape/dtype mismatch between tokens, rot, gate_w, bucket and logits")
+    _check(load_library().lshmoe_hash_gate(_ptr(tokens), _ptr(rot), _ptr(gate_w), T, d, L, r, E, _dtype_code(tokens),
+                                           _ptr(bucket, torch.int64), _ptr(logits, torch.float32), _stream(stream)))
 
 
 @dataclass

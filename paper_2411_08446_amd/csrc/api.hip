@@ -103,7 +103,7 @@ const char* lshmoe_status_string(int status) {
 
 const char* lshmoe_last_error(void) { return g_err; }
 
-int lshmoe_abi_version(void) { return 3; }
+int lshmoe_abi_version(void) { return 4; }
 
 lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E, int32_t L, int32_t r,
                                      lshmoe_dtype dtype, size_t* out_bytes) {
@@ -124,6 +124,26 @@ lshmoe_status lshmoe_hash(const void* tokens, const void* rot, int64_t T, int32_
   if (r > 256) return fail(LSHMOE_ERR_UNSUPPORTED, "r = %d rotated dimensions per hash; the limit is 256", r);
   hipError_t e = lshmoe::launch_hash(tokens, rot, T, d, L, r, dtype == LSHMOE_BF16, bucket, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("hash launch", e);
+  return ok();
+}
+
+lshmoe_status lshmoe_hash_gate(const void* tokens, const void* rot, const void* gate_w, int64_t T, int32_t d, int32_t L,
+                               int32_t r, int32_t E, lshmoe_dtype dtype, uint64_t* bucket, float* logits, void* stream) {
+  if (!tokens || !rot || !gate_w || !bucket || !logits)
+    return fail(LSHMOE_ERR_NULL, "tokens, rot, gate_w, bucket and logits must be non-NULL");
+  if (T <= 0 || d <= 0 || E <= 0)
+    return fail(LSHMOE_ERR_SHAPE, "T, d and E must be positive (T=%lld, d=%d, E=%d)", (long long)T, d, E);
+  if (lshmoe_status st = check_hash_params(L, r)) return st;
+  if (lshmoe_status st = check_row(d, (int)dtype)) return st;
+  if (T >= kMaxAssignments) return fail(LSHMOE_ERR_UNSUPPORTED, "T = %lld tokens; the limit is 2^30 - 1", (long long)T);
+  if (r > 256) return fail(LSHMOE_ERR_UNSUPPORTED, "r = %d rotated dimensions per hash; the limit is 256", r);
+  if (!lshmoe::hash_gate_supported(d, r, E, dtype == LSHMOE_BF16))
+    return fail(LSHMOE_ERR_UNSUPPORTED,
+                "the fused gate needs r a multiple of 8, rows of whole 512-byte blocks and E <= 128 (r=%d, d=%d, E=%d)", r,
+                d, E);
+  hipError_t e = lshmoe::launch_hash_gate(tokens, rot, gate_w, T, d, L, r, E, dtype == LSHMOE_BF16, bucket, logits,
+                                          (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("hash + gate launch", e);
   return ok();
 }
 

@@ -332,11 +332,16 @@ template <int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX> struct Strea
   static constexpr size_t kLdsBytes = ((size_t)(DR + 1) * kSlotsR + (size_t)(DX + 1) * kSlotsX) * 16;
 };
 
-template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX>
+// GATE: E further rows (a gate projection W_g, same layout as R) are appended to the rows of the single hash
+// group; their products are written to logits[T][E] as binary32 instead of entering an arg-max, so that the
+// hash and the gate read the tokens once.  L = 0 computes the gate rows alone.
+template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX, bool GATE = false>
 __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
     const char* __restrict__ tokens, const char* __restrict__ rot, uint64_t* __restrict__ bucket, uint32_t T,
-    int row_pieces, int L, int r, int hpg) {
+    int row_pieces, int L, int r, int hpg, const char* __restrict__ gate_w = nullptr, int E = 0,
+    float* __restrict__ logits = nullptr) {
   using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
+  static_assert(!GATE || HALVES == 1, "the gate rows ride on the unsplit shapes");
   constexpr int WAVES = S::kWaves, TH = WAVES * 64;
   constexpr int LR = S::kRows / 8 / WAVES, LX = S::kTokens / 8 / WAVES;  // direct loads per wave and chunk
   static_assert(S::kRows % (8 * WAVES) == 0 && S::kTokens % (8 * WAVES) == 0, "whole 8-row loads per wave");
@@ -371,18 +376,22 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
   uint64_t b[NTW];
 #pragma unroll
   for (int u = 0; u < NTW; ++u) b[u] = 0;
-  for (int l0 = 0; l0 < L; l0 += hpg) {
-    const int nh = min(hpg, L - l0);
-    const int rows = nh * r;                 // valid rows of R in this group; staging rows past them repeat the last
-    const char* rot_group = rot + (size_t)l0 * r * row_bytes;
-    uint32_t off_a[LR];
+  for (int l0 = 0; l0 < (GATE ? 1 : L); l0 += hpg) {
+    const int nh = GATE ? L : min(hpg, L - l0);
+    const int rows_h = nh * r;               // rows of R in this group
+    const int rows = rows_h + (GATE ? E : 0);  // valid staged rows; staging rows past them repeat the last
+    const char* arow[LR];                    // this lane's piece of the rows it stages (R first, then the gate rows)
 #pragma unroll
-    for (int i = 0; i < LR; ++i) off_a[i] = (uint32_t)min(8 * (wv * LR + i) + sub, rows - 1) * row_bytes + pc * 16;
+    for (int i = 0; i < LR; ++i) {
+      const int row = min(8 * (wv * LR + i) + sub, rows - 1);
+      arow[i] = (GATE && row >= rows_h ? gate_w + (size_t)(row - rows_h) * row_bytes
+                                       : rot + ((size_t)l0 * r + row) * row_bytes) + pc * 16;
+    }
 
     auto stage_r = [&](int chunk) {
       uint4* dst = lds + (chunk % (DR + 1)) * S::kSlotsR + (8 * wv * LR) * kPieces;
 #pragma unroll
-      for (int i = 0; i < LR; ++i) load16_to_lds(rot_group + (size_t)chunk * (kPieces * 16) + off_a[i], dst + 8 * i * kPieces);
+      for (int i = 0; i < LR; ++i) load16_to_lds(arow[i] + (size_t)chunk * (kPieces * 16), dst + 8 * i * kPieces);
     };
     auto stage_x = [&](int chunk) {
       uint4* dst = lds_x + (chunk % (DX + 1)) * S::kSlotsX + (8 * wv * LX) * kPieces;
@@ -506,6 +515,30 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
         }
       }
     }
+    if (GATE) {
+      // rows rows_h .. rows_h + E - 1 are gate logits: a lane holds 4 consecutive ones of its token per register quad
+#pragma unroll
+      for (int u = 0; u < NTW; ++u) {
+        const uint32_t tok = tok_blk + (uint32_t)(g * NTW * 32 + u * 32 + n);
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+#pragma unroll
+          for (int jb = 0; jb < 4; ++jb) {
+            const int e0 = t * 32 + 8 * jb + 4 * h - rows_h;   // rows_h is a multiple of 8: e0 is a multiple of 4
+            if (tok >= T || e0 < 0 || e0 >= E) continue;
+            float* dst = logits + (size_t)tok * E + e0;
+            if (e0 + 3 < E && (E & 3) == 0) {
+              *reinterpret_cast<float4*>(dst) = make_float4(acc[t][u][4 * jb], acc[t][u][4 * jb + 1],
+                                                            acc[t][u][4 * jb + 2], acc[t][u][4 * jb + 3]);
+            } else {
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (e0 + i < E) dst[i] = acc[t][u][4 * jb + i];
+            }
+          }
+        }
+      }
+    }
     if (HALVES == 2) {
       __syncthreads();                       // both halves of every token are in LDS
       if (mh == 0 && h == 0) {
@@ -524,7 +557,7 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
       }
     }
   }
-  if (mh == 0 && h == 0) {
+  if (mh == 0 && h == 0 && (!GATE || L > 0)) {
 #pragma unroll
     for (int u = 0; u < NTW; ++u) {
       const uint32_t tok = tok_blk + (uint32_t)(g * NTW * 32 + u * 32 + n);
@@ -533,12 +566,12 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
   }
 }
 
-template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX>
+template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX, bool GATE = false>
 hipError_t launch_stream(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
-                         hipStream_t stream) {
+                         hipStream_t stream, const char* gate_w = nullptr, int E = 0, float* logits = nullptr) {
   using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
   static_assert(S::kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
-  auto kern = hash_stream_kernel<DT, MTW, NTW, GROUPS, HALVES, DR, DX>;
+  auto kern = hash_stream_kernel<DT, MTW, NTW, GROUPS, HALVES, DR, DX, GATE>;
   static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
   if (!raised.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes);
@@ -546,7 +579,8 @@ hipError_t launch_stream(const char* x, const char* R, uint64_t* bucket, int64_t
     raised.store(true, std::memory_order_release);
   }
   const dim3 grid((uint32_t)((T + S::kTokens - 1) / S::kTokens)), block(S::kWaves * 64);
-  hipLaunchKernelGGL(kern, grid, block, S::kLdsBytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg);
+  hipLaunchKernelGGL(kern, grid, block, S::kLdsBytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg, gate_w, E,
+                     logits);
   return hipGetLastError();
 }
 
@@ -627,6 +661,52 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
 }
 
 }  // namespace
+
+namespace {
+
+// Gate rows (and, when they fit, the hash rows in front of them) on the streaming kernel: mt row tiles per wave.
+template <typename DT>
+hipError_t launch_gate_rows(const char* x, const char* R, const char* W, int64_t T, int row_pieces, int L, int r, int E,
+                            uint64_t* bucket, float* logits, hipStream_t stream) {
+  const int mt = (L * r + E + 31) / 32;
+  const bool big = T >= 24576;
+#define LSHMOE_GATE(MT)                                                                                               \
+  (big ? launch_stream<DT, MT, 1, 4, 1, 3, 4, true>(x, R, bucket, T, row_pieces, L, r, L > 0 ? L : 1, stream, W, E, logits) \
+       : launch_stream<DT, MT, 1, 2, 1, 2, 3, true>(x, R, bucket, T, row_pieces, L, r, L > 0 ? L : 1, stream, W, E, logits))
+  if (mt <= 1) return LSHMOE_GATE(1);
+  if (mt == 2) return LSHMOE_GATE(2);
+  if (mt == 3) return LSHMOE_GATE(3);
+  return LSHMOE_GATE(4);
+#undef LSHMOE_GATE
+}
+
+template <typename DT>
+hipError_t launch_hash_gate_typed(const void* tokens, const void* rot, const void* gate_w, int64_t T, int d, int L, int r,
+                                  int E, uint64_t* bucket, float* logits, hipStream_t stream) {
+  const int row_pieces = (int)((size_t)d * ItemSize<DT>::value / 16);
+  auto x = (const char*)tokens;
+  auto R = (const char*)rot;
+  auto W = (const char*)gate_w;
+  if ((int64_t)L * r + E <= 128)  // one pass over the tokens for both
+    return launch_gate_rows<DT>(x, R, W, T, row_pieces, L, r, E, bucket, logits, stream);
+  // too many rows for one accumulator set: the hash as usual, then the gate rows alone (the tokens are read twice)
+  hipError_t e = launch_typed<DT>(tokens, rot, T, d, L, r, bucket, stream);
+  if (e != hipSuccess) return e;
+  return launch_gate_rows<DT>(x, R, W, T, row_pieces, 0, r, E, bucket, logits, stream);
+}
+
+}  // namespace
+
+bool hash_gate_supported(int d, int r, int E, bool bf16) {
+  const int row_pieces = (int)((size_t)d * (bf16 ? 2 : 4) / 16);
+  return r % 8 == 0 && row_pieces % (kPieces * 4) == 0 && E >= 1 && E <= 128;
+}
+
+hipError_t launch_hash_gate(const void* tokens, const void* rot, const void* gate_w, int64_t T, int d, int L, int r, int E,
+                            bool bf16, uint64_t* bucket, float* logits, hipStream_t stream) {
+  return bf16 ? launch_hash_gate_typed<BF16>(tokens, rot, gate_w, T, d, L, r, E, bucket, logits, stream)
+              : launch_hash_gate_typed<F32>(tokens, rot, gate_w, T, d, L, r, E, bucket, logits, stream);
+}
 
 hipError_t launch_hash(const void* tokens, const void* rot, int64_t T, int d, int L, int r, bool bf16,
                        uint64_t* bucket, hipStream_t stream) {

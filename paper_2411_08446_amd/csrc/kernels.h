@@ -13,6 +13,12 @@ namespace lshmoe {
 hipError_t launch_hash(const void* tokens, const void* rot, int64_t T, int d, int L, int r, bool bf16,
                        uint64_t* bucket, hipStream_t stream);
 
+// Hash plus E rows of a gate projection in one pass over the tokens (logits[T][E], binary32).  Supported shapes:
+// hash_gate_supported (r a multiple of 8, rows of whole 512-byte blocks, E <= 128).
+bool hash_gate_supported(int d, int r, int E, bool bf16);
+hipError_t launch_hash_gate(const void* tokens, const void* rot, const void* gate_w, int64_t T, int d, int L, int r, int E,
+                            bool bf16, uint64_t* bucket, float* logits, hipStream_t stream);
+
 // ---- step 2: group ------------------------------------------------------
 constexpr int kSortTile = 2048;            // assignments per sort tile
 constexpr int kSegTile = 1024;             // sorted positions per cluster-numbering tile

@@ -30,7 +30,7 @@ def _declared_symbols():
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
     assert {"lshmoe_hash", "lshmoe_compress", "lshmoe_decompress", "lshmoe_decompress_combine", "lshmoe_workspace_bytes",
-            "lshmoe_backward_workspace_bytes", "lshmoe_decompress_backward", "lshmoe_compress_backward",
+            "lshmoe_backward_workspace_bytes", "lshmoe_decompress_backward", "lshmoe_compress_backward", "lshmoe_hash_gate",
             "lshmoe_status_string", "lshmoe_last_error", "lshmoe_abi_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -92,6 +92,12 @@ def test_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, None, 16, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, p, 16, 64, 2, 1, 4, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, p, 0, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_SHAPE
+    # hash + gate
+    assert lib.lshmoe_hash_gate(p, p, None, 16, 256, 2, 8, 4, 1, p, p, None) == lsh.LSHMOE_ERR_NULL
+    assert lib.lshmoe_hash_gate(p, p, p, 16, 256, 2, 8, 0, 1, p, p, None) == lsh.LSHMOE_ERR_SHAPE
+    assert lib.lshmoe_hash_gate(p, p, p, 16, 256, 2, 8, 129, 1, p, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED   # E > 128
+    assert lib.lshmoe_hash_gate(p, p, p, 16, 256, 2, 12, 4, 1, p, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED    # r % 8
+    assert lib.lshmoe_hash_gate(p, p, p, 16, 264, 2, 8, 4, 1, p, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED     # 528-byte rows
     # backward
     need = lsh.lshmoe_backward_workspace_bytes(16, 64, 2, lsh.LSHMOE_BF16)
     assert 0 < need <= lsh.lshmoe_workspace_bytes(16, 64, 2, 4, 2, 8, lsh.LSHMOE_BF16)   # a compress workspace is enough

@@ -299,6 +299,39 @@ def test_backward_long_clusters(H, dtype):
     H.check_backward(run, T, d, 2, dtype, seed=38)
 
 
+# ------------------------------------------------------------------ hash fused with the gate projection
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,L,r,E", [(32768 + 9, 3, 32, 32),    # GPT shape: 96 + 32 rows, one pass, 128-token workgroups
+                                     (16384 + 3, 2, 32, 16),    # RoBERTa shape: 64-token workgroups
+                                     (9000, 1, 8, 5),           # E not a multiple of 4, a single tile
+                                     (70000, 4, 64, 64),        # T5 shape: hash as usual, then the gate rows alone
+                                     (100, 2, 16, 128),         # tiny T, widest gate
+                                     (5000, 12, 8, 30)])        # 96 + 30 rows
+def test_hash_gate(H, dtype, T, L, r, E):
+    import oracle
+    d = 256 if dtype == "bf16" else 128
+    rng = np.random.default_rng(51)
+    tokens = synth.f32_to_storage(rng.standard_normal((T, d)).astype(np.float32), dtype)
+    rot = synth.f32_to_storage(rng.standard_normal((L, r, d)).astype(np.float32), dtype)
+    gate = synth.f32_to_storage(rng.standard_normal((E, d)).astype(np.float32), dtype)
+    xt, rt, gt = H.to_device(tokens, dtype), H.to_device(rot, dtype), H.to_device(gate, dtype)
+    bt = torch.full((T + 4,), -1, dtype=torch.int64, device="cuda")
+    lt = torch.full((T + 2, E), float("nan"), dtype=torch.float32, device="cuda")
+    H.lsh.lshmoe_hash_gate(xt, rt, gt, bt[:T], lt[:T])
+    torch.cuda.synchronize()
+    assert np.all(bt[T:].cpu().numpy() == -1) and torch.isnan(lt[T:]).all(), "nothing is written past T"
+    bucket = bt[:T].cpu().numpy().view(np.uint64)
+    H.check_hash(bucket, tokens, rot, dtype)
+    plain = torch.empty(T, dtype=torch.int64, device="cuda")
+    H.lsh.lshmoe_hash(xt, rt, plain)                       # the fused call hashes exactly like the plain one
+    torch.cuda.synchronize()
+    assert np.array_equal(plain.cpu().numpy().view(np.uint64), bucket)
+    ref = oracle.gate_logits_ref(tokens, gate, dtype)
+    got = lt[:T].cpu().numpy().astype(np.float64)
+    err = oracle.row_rel_err(got, ref)
+    assert err.max() <= 1e-5, "gate logits: row %d off by %.3g" % (int(err.argmax()), err.max())
+
+
 def test_path_replays_from_a_graph(H):
     # the calls only enqueue kernels on the caller's stream (no allocation, no host synchronisation, no memset
     # nodes), so a step can be captured once and replayed: three replays on fresh inputs, with eager work and

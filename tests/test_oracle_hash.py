@@ -242,3 +242,22 @@ def test_bf16_inputs_are_widened_exactly():
     b = hash_ref(x32, R32, "f32")
     for u, v in zip(a, b):
         assert np.array_equal(u, v)
+
+
+def test_gate_logits_against_python_loops_and_unit_vectors():
+    # E != d and T != E, so a transposed operand cannot pass
+    from oracle import gate_logits_ref, widen
+    rng = np.random.default_rng(11)
+    T, d, E = 7, 12, 5
+    for dtype in ("f32", "bf16"):
+        x = synth.f32_to_storage(rng.standard_normal((T, d)).astype(np.float32), dtype)
+        w = synth.f32_to_storage(rng.standard_normal((E, d)).astype(np.float32), dtype)
+        got = gate_logits_ref(x, w, dtype)
+        assert got.shape == (T, E) and got.dtype == np.float64
+        x64, w64 = widen(x, dtype), widen(w, dtype)
+        for t in range(T):
+            for e in range(E):
+                assert abs(got[t, e] - sum(float(x64[t, i]) * float(w64[e, i]) for i in range(d))) < 1e-12
+        unit = np.zeros((E, d), np.float32)
+        unit[np.arange(E), [3, 0, 11, 7, 5]] = 1.0          # gate row e picks out one coordinate
+        assert np.array_equal(gate_logits_ref(x, synth.f32_to_storage(unit, dtype), dtype), x64[:, [3, 0, 11, 7, 5]])
