@@ -36,9 +36,9 @@ namespace lshmoe {
 namespace {
 
 constexpr int kSortThreads = 256;
-constexpr int kSortItems = kSortTile / kSortThreads;  // 8
-constexpr int kGroupsPerTile = kSortTile / kWave;     // 32 waves' worth of keys
-constexpr int kGhStride = kGroupsPerTile + 1;          // per-bin row of group counts, padded against bank conflicts
+// A sort tile holds TILE keys (kSortTile = 2048 unless the plan picks a smaller one for small inputs, so that
+// more workgroups share the work): TILE / 256 keys per thread, TILE / 64 wave-sized groups whose per-bin
+// counts form a row of TILE / 64 + 1 words (padded against bank conflicts) in LDS.
 constexpr int kTableBatch = 32;                        // count-table rows a thread fetches per round trip
 constexpr int kSegThreads = 256;
 constexpr int kSegItems = kSegTile / kSegThreads;     // 4
@@ -92,18 +92,19 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
 
 // Tile histogram of one pass.  FUSED: row `tile` of a tile-major table.  Otherwise: column `tile` of a
 // bin-major table (scanned next).
-template <bool FIRST, bool FUSED>
+template <bool FIRST, bool FUSED, int TILE = kSortTile>
 __global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(KeySource src, uint32_t N, int shift, uint32_t mask,
                                                                  uint32_t nblk, uint32_t* __restrict__ table,
                                                                  uint32_t* __restrict__ clear = nullptr,
                                                                  uint32_t clear_n = 0) {
+  constexpr int kSortItems = TILE / kSortThreads;
   __shared__ uint32_t h[kGroupBins];
   if (clear != nullptr && blockIdx.x * kSortThreads + threadIdx.x < clear_n)  // counters a later kernel adds to
     clear[blockIdx.x * kSortThreads + threadIdx.x] = 0;
   h[threadIdx.x] = 0;
   h[threadIdx.x + 256] = 0;
   __syncthreads();
-  const uint32_t base = blockIdx.x * kSortTile;
+  const uint32_t base = blockIdx.x * TILE;
   uint64_t key[kSortItems];
   int32_t idx[kSortItems];
 #pragma unroll
@@ -196,14 +197,15 @@ struct PassArgs {
   uint32_t* chunk_tbl;    // then the number of chunks and whether a bin has several; and the chunk table
 };
 
-template <bool FIRST, bool FUSED>
+template <bool FIRST, bool FUSED, int TILE = kSortTile>
 __global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(KeySource src, uint32_t N, PassArgs a,
                                                                     uint64_t* __restrict__ dst_key,
                                                                     int32_t* __restrict__ dst_idx) {
+  constexpr int kSortItems = TILE / kSortThreads, kGroupsPerTile = TILE / kWave, kGhStride = kGroupsPerTile + 1;
   extern __shared__ uint32_t gh[];  // [kGroupBins][kGhStride] per-bin counts of each 64-key group, then start offsets
   __shared__ uint32_t wave_sum[4];
   __shared__ uint32_t part[2][2][kGroupBins];  // FUSED: [before/total][tile parity][bin]
-  const uint32_t base = blockIdx.x * kSortTile;
+  const uint32_t base = blockIdx.x * TILE;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   uint64_t key[kSortItems];
@@ -906,12 +908,11 @@ int bits_for(uint64_t max_value) {  // number of bits needed to hold max_value
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-constexpr size_t kScatterLds = (size_t)kGroupBins * kGhStride * 4;  // 66 KB
-
-template <bool FIRST, bool FUSED>
+template <bool FIRST, bool FUSED, int TILE = kSortTile>
 hipError_t launch_scatter(const KeySource& src, uint32_t N, const PassArgs& a, uint64_t* dkey, int32_t* didx,
                           hipStream_t stream) {
-  auto kern = sort_scatter_kernel<FIRST, FUSED>;
+  constexpr size_t kScatterLds = (size_t)kGroupBins * (TILE / kWave + 1) * 4;  // 66 KB for tiles of 2048
+  auto kern = sort_scatter_kernel<FIRST, FUSED, TILE>;
   static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
   if (!raised.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLds);
@@ -941,10 +942,15 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
     p.width[i] = w < 1 ? 1 : w;
     at += w;
   }
+  p.tile = kSortTile;
   p.sort_blocks = (uint32_t)((p.N + kSortTile - 1) / kSortTile);
   p.seg_blocks = (uint32_t)((p.N + kSegTile - 1) / kSegTile);
   p.fused = p.sort_blocks <= (uint32_t)kFusedMaxTiles;
   p.msd = p.fused && p.N > kSmallMaxN && bits > kMaxDigitBits;
+  if (p.msd && p.N < 131072) {  // small inputs: smaller tiles put more workgroups on the one global pass
+    p.tile = p.N <= 32768 ? 512 : 1024;
+    p.sort_blocks = (uint32_t)((p.N + p.tile - 1) / p.tile);
+  }
   if (p.msd) {
     p.top_width = kMaxDigitBits;
     p.top_shift = bits - kMaxDigitBits;
@@ -974,9 +980,10 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
   p.off_binstart = off;
   off = align256(off + ((size_t)kGroupBins + 3) * 4);
   p.off_chunktbl = off;
-  off = align256(off + ((size_t)kGroupBins + p.sort_blocks) * 4);  // a chunk per non-empty bin and per kBinChunk keys
+  const size_t max_chunks = (size_t)kGroupBins + (size_t)((p.N + kBinChunk - 1) / kBinChunk);  // one per non-empty bin and per kBinChunk keys
+  off = align256(off + max_chunks * 4);
   p.off_chunkheads = off;
-  off = align256(off + ((size_t)kGroupBins + p.sort_blocks) * 16);
+  off = align256(off + max_chunks * 16);
   const size_t windows = 2 * (size_t)((p.N + kCentroidWindow - 1) / kCentroidWindow);
   p.off_partial = off;
   off = align256(off + windows * (size_t)d * 4);
@@ -1029,9 +1036,15 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     a.bin_start = bin_start;
     a.chunk_tbl = (uint32_t*)(ws + plan.off_chunktbl);
     // the histogram kernel also clears the per-tile head counts that the bin kernels add to
-    hipLaunchKernelGGL((sort_hist_kernel<true, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table,
-                       blocksum, plan.seg_blocks + 1);
-    hipError_t e = launch_scatter<true, true>(src, N, a, keybuf[0], idxbuf[0], stream);
+    hipError_t e = hipSuccess;
+#define LSHMOE_GLOBAL_PASS(TILE)                                                                                     \
+    hipLaunchKernelGGL((sort_hist_kernel<true, true, TILE>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table, \
+                       blocksum, plan.seg_blocks + 1);                                                                  \
+    e = launch_scatter<true, true, TILE>(src, N, a, keybuf[0], idxbuf[0], stream)
+    if (plan.tile == 512) { LSHMOE_GLOBAL_PASS(512); }
+    else if (plan.tile == 1024) { LSHMOE_GLOBAL_PASS(1024); }
+    else { LSHMOE_GLOBAL_PASS(kSortTile); }
+#undef LSHMOE_GLOBAL_PASS
     if (e != hipSuccess) return e;
     BinSortArgs b{};
     b.bin_start = bin_start;
@@ -1049,8 +1062,7 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     b.sub_mask = (1u << sub_bits) - 1u;
     b.tile_heads = blocksum;
     b.chunk_heads = (uint4*)(ws + plan.off_chunkheads);
-    static_assert(kBinChunk == kSortTile, "the chunk bound below counts sort tiles");
-    const dim3 chunks((uint32_t)kGroupBins + nblk), threads(kBinThreads);
+    const dim3 chunks((uint32_t)kGroupBins + (N + kBinChunk - 1) / kBinChunk), threads(kBinThreads);
     hipLaunchKernelGGL(bin_sort_kernel, chunks, threads, kBinSortLds, stream, b);
     hipLaunchKernelGGL(bin_merge_kernel, dim3(chunks.x * kMergeSlices), threads, 0, stream, b);
     // the heads per numbering tile are known: number the clusters (the tile count is within kSelfPrefixMaxTiles here)

@@ -38,7 +38,8 @@ struct GroupPlan {
   int top_shift, top_width;        // msd: the global pass's digit
   int low_passes;                  // msd: radix passes over the remaining bits
   int low_shift[8], low_width[8];
-  uint32_t sort_blocks;  // tiles of kSortTile assignments
+  int tile;              // assignments per sort tile (kSortTile, or less on small inputs)
+  uint32_t sort_blocks;  // sort tiles
   uint32_t seg_blocks;   // tiles of kSegTile sorted positions
   // byte offsets into the workspace
   size_t off_key[2], off_idx[2], off_table, off_blocksum, off_binstart, off_chunktbl, off_chunkheads;
