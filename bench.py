@@ -138,7 +138,8 @@ def main():
         if ev: ev[1].record()
         lsh.lshmoe_compress(x, expert, bucket, E, L, r, o)
         if ev: ev[2].record()
-        lsh.lshmoe_decompress(x, o.centroids, ecs[c], o.seg_of, o.seg_offsets, k, ys[c])
+        lsh.lshmoe_decompress(x, o.centroids, ecs[c], o.seg_of, o.seg_offsets, k, ys[c], perm=o.perm,
+                              num_segments=o.num_segments)
         if ev: ev[3].record()
 
     if args.calibration_copy_mib > 0:

@@ -186,14 +186,21 @@ lshmoe_status lshmoe_compress(const void* tokens, const int32_t* expert, const u
  *   seg_offsets [S+1]   in   int32 or NULL.  When given, one-member clusters skip
  *                            the token and centroid reads (their difference is
  *                            exactly zero); the result is the same either way.
+ *   perm [N], num_segments [1]  in  int32 or both NULL, as written by lshmoe_compress.
+ *                            When given and the clusters are long on average
+ *                            (S / N < 0.65), the rows are produced in cluster order,
+ *                            which fetches every cluster's expert-output and centroid
+ *                            row once instead of once per member; the result is the
+ *                            same either way.
  *   out         [T, k, d] out dtype, assignment order
  *
- * Errors: NULL pointer (seg_offsets excepted); T, d, k <= 0; N >= 2^30
+ * Errors: NULL pointer (seg_offsets excepted; perm and num_segments both or neither); T, d, k <= 0; N >= 2^30
  * (UNSUPPORTED); unknown flag bits (UNSUPPORTED); row size not a multiple of
  * 16 bytes (UNSUPPORTED); launch failure (HIP).
  */
 lshmoe_status lshmoe_decompress(const void* tokens, const void* centroids, const void* expert_out,
                                 const int32_t* seg_of, const int32_t* seg_offsets,
+                                const int32_t* perm, const int32_t* num_segments,
                                 int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, uint32_t flags,
                                 void* out, void* stream);
 

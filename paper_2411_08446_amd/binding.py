@@ -22,7 +22,7 @@ LSHMOE_ERR_HIP = 5
 LSHMOE_F32 = 0
 LSHMOE_BF16 = 1
 LSHMOE_FLAG_NO_RESIDUAL = 1
-ABI_VERSION = 4   # of include/lshmoe.h as this binding declares it
+ABI_VERSION = 5   # of include/lshmoe.h as this binding declares it
 
 
 class LshmoeError(RuntimeError):
@@ -64,7 +64,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.lshmoe_compress.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_int,
                                     vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.lshmoe_decompress.restype = ctypes.c_int
-    lib.lshmoe_decompress.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
+    lib.lshmoe_decompress.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
     lib.lshmoe_decompress_combine.restype = ctypes.c_int
     lib.lshmoe_decompress_combine.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
     lib.lshmoe_backward_workspace_bytes.restype = ctypes.c_int
@@ -189,15 +189,19 @@ def lshmoe_compress(tokens: torch.Tensor, expert: torch.Tensor, bucket: torch.Te
 
 
 def lshmoe_decompress(tokens: torch.Tensor, centroids: torch.Tensor, expert_out: torch.Tensor, seg_of: torch.Tensor,
-                      seg_offsets, k: int, out: torch.Tensor, flags: int = 0, stream=None) -> None:
+                      seg_offsets, k: int, out: torch.Tensor, flags: int = 0, stream=None, perm=None,
+                      num_segments=None) -> None:
     T, d = tokens.shape
     if out.numel() != T * k * d or out.dtype != tokens.dtype or seg_of.numel() != T * k:
         raise ValueError("out must hold [T, k, d] elements of the token dtype and seg_of N entries")
     if centroids.dtype != tokens.dtype or expert_out.dtype != tokens.dtype:
         raise TypeError("centroids and expert_out must have the token dtype")
+    if perm is not None and perm.numel() != T * k:
+        raise ValueError("perm must have T*k entries")
     _check(load_library().lshmoe_decompress(
         _ptr(tokens), _ptr(centroids), _ptr(expert_out), _ptr(seg_of, torch.int32),
-        _ptr(seg_offsets, torch.int32), T, d, k, _dtype_code(tokens), flags, _ptr(out), _stream(stream)))
+        _ptr(seg_offsets, torch.int32), _ptr(perm, torch.int32), _ptr(num_segments, torch.int32),
+        T, d, k, _dtype_code(tokens), flags, _ptr(out), _stream(stream)))
 
 
 def lshmoe_decompress_combine(tokens: torch.Tensor, centroids: torch.Tensor, expert_out: torch.Tensor,

@@ -103,7 +103,7 @@ const char* lshmoe_status_string(int status) {
 
 const char* lshmoe_last_error(void) { return g_err; }
 
-int lshmoe_abi_version(void) { return 4; }
+int lshmoe_abi_version(void) { return 5; }
 
 lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E, int32_t L, int32_t r,
                                      lshmoe_dtype dtype, size_t* out_bytes) {
@@ -174,8 +174,9 @@ lshmoe_status lshmoe_compress(const void* tokens, const int32_t* expert, const u
 }
 
 lshmoe_status lshmoe_decompress(const void* tokens, const void* centroids, const void* expert_out,
-                                const int32_t* seg_of, const int32_t* seg_offsets, int64_t T, int32_t d, int32_t k,
-                                lshmoe_dtype dtype, uint32_t flags, void* out, void* stream) {
+                                const int32_t* seg_of, const int32_t* seg_offsets, const int32_t* perm,
+                                const int32_t* num_segments, int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype,
+                                uint32_t flags, void* out, void* stream) {
   if (!tokens || !centroids || !expert_out || !seg_of || !out)
     return fail(LSHMOE_ERR_NULL, "an input or output pointer is NULL");
   if (T <= 0 || d <= 0 || k <= 0)
@@ -186,8 +187,10 @@ lshmoe_status lshmoe_decompress(const void* tokens, const void* centroids, const
     return fail(LSHMOE_ERR_UNSUPPORTED, "N = T*k = %lld assignments; the limit is 2^30 - 1", (long long)(T * (int64_t)k));
   if ((uint64_t)T * (uint64_t)k * ((size_t)d * item_size((int)dtype) / 16) > 0xffffff00ull)
     return fail(LSHMOE_ERR_UNSUPPORTED, "N*d is too large for one launch");
-  hipError_t e = lshmoe::launch_restore(tokens, centroids, expert_out, seg_of, seg_offsets, out, T * (int64_t)k, k, d,
-                                        dtype == LSHMOE_BF16, flags, (hipStream_t)stream);
+  if ((perm == nullptr) != (num_segments == nullptr))
+    return fail(LSHMOE_ERR_NULL, "perm and num_segments are given together or not at all");
+  hipError_t e = lshmoe::launch_restore(tokens, centroids, expert_out, seg_of, seg_offsets, perm, num_segments, out,
+                                        T * (int64_t)k, k, d, dtype == LSHMOE_BF16, flags, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("restore launch", e);
   return ok();
 }

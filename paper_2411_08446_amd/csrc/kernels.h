@@ -65,9 +65,11 @@ hipError_t launch_centroid(const void* rows, const int32_t* perm, const int32_t*
                            int k, int d, bool bf16, bool mean, hipStream_t stream);
 
 // ---- step 4: restore ----------------------------------------------------
+// perm and num_segments (both optional): allow the kernel to walk the rows in cluster order when clusters are long.
 hipError_t launch_restore(const void* tokens, const void* centroids, const void* expert_out,
-                          const int32_t* seg_of, const int32_t* seg_offsets, void* out, int64_t N, int k, int d,
-                          bool bf16, uint32_t flags, hipStream_t stream);
+                          const int32_t* seg_of, const int32_t* seg_offsets, const int32_t* perm,
+                          const int32_t* num_segments, void* out, int64_t N, int k, int d, bool bf16, uint32_t flags,
+                          hipStream_t stream);
 
 hipError_t launch_restore_combine(const void* tokens, const void* centroids, const void* expert_out,
                                   const int32_t* seg_of, const int32_t* seg_offsets, const float* gate_weight,

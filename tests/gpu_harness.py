@@ -118,7 +118,13 @@ def run_and_check(tokens: np.ndarray, rot: np.ndarray, expert: np.ndarray, E: in
     yt = torch.full((T, k, d), float("nan"), dtype=xt.dtype, device="cuda")
     lsh.lshmoe_decompress(xt, out.centroids, ec_t, out.seg_of, out.seg_offsets if use_seg_offsets else None,
                           k, yt, flags=flags)
+    # the same call with perm and the cluster count (cluster order when clusters are long): identical output
+    yt2 = torch.full((T, k, d), float("nan"), dtype=xt.dtype, device="cuda")
+    lsh.lshmoe_decompress(xt, out.centroids, ec_t, out.seg_of, out.seg_offsets if use_seg_offsets else None,
+                          k, yt2, flags=flags, perm=out.perm, num_segments=out.num_segments)
     torch.cuda.synchronize()
+    assert torch.equal(yt.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       yt2.view(torch.int16 if dtype == "bf16" else torch.int32)), "row order must not change the result"
     y_gpu = to_storage(yt.view(N, d), dtype)
     y_ref = oracle.restore_ref(tokens, c_gpu, ec, g["seg_of"], k, dtype, no_residual=bool(flags & 1))
     assert_rows_close(y_gpu, y_ref, dtype, "restore")

@@ -85,10 +85,11 @@ def test_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.lshmoe_compress(p, p, p, 16, 64, 1, 4, 2, 8, 1, *ptrs, 0x1000, 64, None) == lsh.LSHMOE_ERR_WORKSPACE
     assert lib.lshmoe_compress(p, None, p, 16, 64, 1, 4, 2, 8, 1, *ptrs, 0x1000, 1 << 30, None) == lsh.LSHMOE_ERR_NULL
     assert lib.lshmoe_compress(p, p, p, 16, 64, 5, 4, 2, 8, 1, *ptrs, 0x1000, 1 << 30, None) == lsh.LSHMOE_ERR_SHAPE
-    assert lib.lshmoe_decompress(p, p, p, None, None, 16, 64, 1, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL
-    assert lib.lshmoe_decompress(p, p, p, p, None, 16, 64, 0, 1, 0, p, None) == lsh.LSHMOE_ERR_SHAPE
-    assert lib.lshmoe_decompress(p, p, p, p, None, 16, 64, 1, 1, 2, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
-    assert lib.lshmoe_decompress(p, p, p, p, None, 16, 63, 1, 0, 0, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
+    assert lib.lshmoe_decompress(p, p, p, None, None, None, None, 16, 64, 1, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL
+    assert lib.lshmoe_decompress(p, p, p, p, None, None, None, 16, 64, 0, 1, 0, p, None) == lsh.LSHMOE_ERR_SHAPE
+    assert lib.lshmoe_decompress(p, p, p, p, None, None, None, 16, 64, 1, 1, 2, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
+    assert lib.lshmoe_decompress(p, p, p, p, None, None, None, 16, 63, 1, 0, 0, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
+    assert lib.lshmoe_decompress(p, p, p, p, None, p, None, 16, 64, 1, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL   # perm alone
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, None, 16, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_NULL
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, p, 16, 64, 2, 1, 4, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
     assert lib.lshmoe_decompress_combine(p, p, p, p, None, p, 0, 64, 2, 1, 0, p, None) == lsh.LSHMOE_ERR_SHAPE

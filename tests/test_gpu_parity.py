@@ -351,7 +351,8 @@ def test_path_replays_from_a_graph(H):
     def step():
         lsh.lshmoe_hash(x, rot, bucket)
         lsh.lshmoe_compress(x, expert, bucket, E, L, r, out)
-        lsh.lshmoe_decompress(x, out.centroids, ec, out.seg_of, out.seg_offsets, k, y)
+        lsh.lshmoe_decompress(x, out.centroids, ec, out.seg_of, out.seg_offsets, k, y, perm=out.perm,
+                              num_segments=out.num_segments)
 
     def load(w):
         x.copy_(H.to_device(w.tokens, cfg.dtype))
