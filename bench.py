@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="t5", choices=["tiny", "swin", "roberta", "gpt", "t5"])
     ap.add_argument("--gate", default=None, help="override the gate kind (e.g. 'content' for the supplementary run)")
+    ap.add_argument("--centers", type=int, default=None, help="override the number of mixture centers (supplementary runs)")
+    ap.add_argument("--sigma", type=float, default=None, help="override the within-cluster noise (supplementary runs)")
     ap.add_argument("--copies", type=int, default=2, help="independent input copies rotated between steps")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -98,7 +100,8 @@ def main():
     from workloads import synth
 
     lsh.load_library()
-    cfg = synth.config(args.workload, **({"gate": args.gate} if args.gate else {}))
+    over = {key: val for key, val in (("gate", args.gate), ("centers", args.centers), ("sigma", args.sigma)) if val is not None}
+    cfg = synth.config(args.workload, **over)
     w = synth.generate(cfg)
     T, d, k, E, L, r, N = cfg.T, cfg.d, cfg.k, cfg.E, cfg.L, cfg.r, cfg.N
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16

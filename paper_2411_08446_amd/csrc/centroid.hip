@@ -22,46 +22,70 @@ template <int LPR> __device__ __forceinline__ int32_t uniform(int32_t v) {
   return LPR == 64 ? __builtin_amdgcn_readfirstlane(v) : v;  // a whole wave shares the value: keep it scalar
 }
 
-// Compensated sum of the token rows at sorted positions [a, b) (wave-wide, lanes stride over the 16-byte
-// pieces of the row), written as binary32 to out_row.  Kept small in registers on purpose: the kernel's
-// occupancy is set by its largest path, and this one runs for long clusters only.
+// Compensated sum of the token rows at sorted positions [a, b), wave-wide: lanes stride over the 16-byte pieces
+// of the row, eight rows in flight (a walk by one wave is bound by memory latency).  emit(c, acc) receives the
+// sums of piece c.  Kept small in registers on purpose: the kernel's occupancy is set by its largest path.
+template <typename DT, typename Emit>
+__device__ __forceinline__ void row_sum_kahan(const char* __restrict__ tokens, const int32_t* __restrict__ perm,
+                                              int32_t a, int32_t b, uint32_t k, uint32_t cpr, size_t row_bytes,
+                                              Emit emit) {
+  constexpr int E = Piece<DT>::kElems;
+  constexpr int kRows = 8;
+  const uint32_t lane = threadIdx.x & 63;
+  // every lane of the wave walks every pass, also lanes past the end of the row (they hold member ids, see
+  // below, and only skip the row loads): the loop bounds are wave-uniform
+  for (uint32_t c0 = 0; c0 < cpr; c0 += 64) {
+    const uint32_t c = c0 + lane;
+    const bool on = c < cpr;
+    float acc[E], comp[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = comp[i] = 0.0f;
+    // the member ids come 64 at a time, one coalesced load per block (lane l holds the id of row p0 + l), so
+    // that a round of row loads does not wait for an id load first; the next block is fetched a block ahead
+    int32_t ids = perm[min(a + (int32_t)lane, b - 1)];
+    for (int32_t p0 = a; p0 < b; p0 += 64) {
+      const int32_t ids_now = ids;
+      if (p0 + 64 < b) ids = perm[min(p0 + 64 + (int32_t)lane, b - 1)];
+      const int32_t rows_here = min(64, b - p0);
+      for (int32_t j = 0; j < rows_here; j += kRows) {
+        uint4 q[kRows];
+#pragma unroll
+        for (int u = 0; u < kRows; ++u) {
+          const int32_t jj = min(j + u, rows_here - 1);  // the surplus rows of the last round are loaded and not added
+          const uint32_t id = (uint32_t)__builtin_amdgcn_readlane(ids_now, jj);
+          q[u] = on ? load16(tokens + (size_t)(id / k) * row_bytes + c * 16) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kRows; ++u) {
+          if (j + u < rows_here) {
+            float x[E];
+            Piece<DT>::widen(q[u], x);
+#pragma unroll
+            for (int i = 0; i < E; ++i) {
+              const float y = x[i] - comp[i];
+              const float t = acc[i] + y;
+              comp[i] = (t - acc[i]) - y;
+              acc[i] = t;
+            }
+          }
+        }
+      }
+    }
+    if (on) emit(c, acc);
+  }
+}
+
+// ... written as binary32 to out_row: the sum of one window of a long cluster.
 template <typename DT>
 __device__ __forceinline__ void window_sum(const char* __restrict__ tokens, const int32_t* __restrict__ perm,
                                            int32_t a, int32_t b, uint32_t k, uint32_t cpr, size_t row_bytes,
                                            float* __restrict__ out_row) {
   constexpr int E = Piece<DT>::kElems;
-  constexpr int kRows = 8;
-  const uint32_t lane = threadIdx.x & 63;
-  for (uint32_t c = lane; c < cpr; c += 64) {
-    float acc[E], comp[E];
-#pragma unroll
-    for (int i = 0; i < E; ++i) acc[i] = comp[i] = 0.0f;
-    for (int32_t p = a; p < b; p += kRows) {
-      uint4 q[kRows];
-#pragma unroll
-      for (int u = 0; u < kRows; ++u) {
-        const int32_t pp = min(p + u, b - 1);  // the surplus rows of the last round are loaded and not added
-        q[u] = load16(tokens + (size_t)((uint32_t)__builtin_amdgcn_readfirstlane(perm[pp]) / k) * row_bytes + c * 16);
-      }
-#pragma unroll
-      for (int u = 0; u < kRows; ++u) {
-        if (p + u < b) {
-          float x[E];
-          Piece<DT>::widen(q[u], x);
-#pragma unroll
-          for (int i = 0; i < E; ++i) {
-            const float y = x[i] - comp[i];
-            const float t = acc[i] + y;
-            comp[i] = (t - acc[i]) - y;
-            acc[i] = t;
-          }
-        }
-      }
-    }
+  row_sum_kahan<DT>(tokens, perm, a, b, k, cpr, row_bytes, [&](uint32_t c, const float (&acc)[E]) {
 #pragma unroll
     for (int i = 0; i < E; i += 4)
       *(float4*)(out_row + (size_t)c * E + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
-  }
+  });
 }
 
 // A cluster with more than kCentroidWindow members is summed by several waves: the sorted positions are cut into
@@ -145,7 +169,18 @@ __global__ __launch_bounds__(256) void centroid_kernel(
   if (s < S) {
     const int32_t lo = uniform<LPR>(seg_offsets[s]), hi = uniform<LPR>(seg_offsets[s + 1]);
     const int32_t n = hi - lo;
-    if (n <= kCentroidWindow) {
+    if (LPR == 64 && n > kPlainSumMax && n <= kCentroidWindow) {
+      // a whole wave on a cluster of 17 .. kCentroidWindow members: compensated sum, eight rows in flight
+      char* dst = centroids + (size_t)s * row_bytes;
+      const float fn = (float)n;
+      row_sum_kahan<DT>(tokens, perm, lo, hi, k, cpr, row_bytes, [&](uint32_t c, float (&acc)[E]) {
+        if (mean) {
+#pragma unroll
+          for (int i = 0; i < E; ++i) acc[i] /= fn;
+        }
+        store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
+      });
+    } else if (n <= kCentroidWindow) {
       const char* first = tokens + (size_t)((uint32_t)uniform<LPR>(perm[lo]) / k) * row_bytes;
       char* dst = centroids + (size_t)s * row_bytes;
       for (uint32_t c = lane % LPR; c < cpr; c += LPR) {
