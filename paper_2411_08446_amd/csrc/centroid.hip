@@ -17,6 +17,10 @@ namespace lshmoe {
 namespace {
 
 constexpr int kPlainSumMax = 16;  // members summed without compensation
+constexpr int kCoopMin = 32;      // clusters with more members (up to kWindowMin) are shared by the workgroup's waves
+constexpr int kWindowMin = 1024;  // clusters with more members are cut into windows of kCentroidWindow positions
+static_assert(kWindowMin >= kCentroidWindow, "a window meets at most two windowed clusters only if they are longer than it");
+constexpr size_t kCoopMaxLds = 32 * 1024;  // more LDS per workgroup would cut the occupancy of the common path
 
 template <int LPR> __device__ __forceinline__ int32_t uniform(int32_t v) {
   return LPR == 64 ? __builtin_amdgcn_readfirstlane(v) : v;  // a whole wave shares the value: keep it scalar
@@ -88,7 +92,7 @@ __device__ __forceinline__ void window_sum(const char* __restrict__ tokens, cons
   });
 }
 
-// A cluster with more than kCentroidWindow members is summed by several waves: the sorted positions are cut into
+// A cluster with more than kWindowMin members is summed by many waves: the sorted positions are cut into
 // aligned blocks of kCentroidWindow; the wave that owns block m sums the part of the block that belongs to the
 // long cluster containing the block's first position (slot 2m) and the part that belongs to a long cluster
 // starting inside the block (slot 2m + 1; there is at most one, since a long cluster is longer than a block).
@@ -158,19 +162,77 @@ template <typename DT, int LPR>
 __global__ __launch_bounds__(256) void centroid_kernel(
     const char* __restrict__ tokens, const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_offsets,
     const int32_t* __restrict__ seg_of, const int32_t* __restrict__ num_segments, char* __restrict__ centroids,
-    float* partial, uint32_t* counters, uint32_t N, uint32_t k, uint32_t cpr, uint32_t mean) {
+    float* partial, uint32_t* counters, uint32_t N, uint32_t k, uint32_t cpr, uint32_t mean, uint32_t coop) {
   constexpr int G = 64 / LPR;  // clusters handled side by side by one wave
   constexpr int E = Piece<DT>::kElems;
+  extern __shared__ float coop_sum[];  // coop: [4 waves][cpr * E] partial sums of a cluster the workgroup shares
   const uint32_t S = (uint32_t)*num_segments;
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t wave = (blockIdx.x * 256u + threadIdx.x) >> 6;
   const uint32_t s = wave * G + lane / LPR;
   const size_t row_bytes = (size_t)cpr * 16;
+  // Clusters of kCoopMin+1 .. kWindowMin members (whole-wave rows only): a single wave walking such a
+  // cluster is bound by memory latency (one round of 8 rows per ~2 us), and when a few hundred of them hold
+  // most of the assignments the kernel waits for them.  The four waves of the workgroup therefore share each
+  // such cluster among the workgroup's four: a quarter of the members each, joined through LDS in wave order.
+  const bool shares = LPR == 64 && coop != 0;
+  auto shared_size = [&](int32_t n) { return shares && n > kCoopMin && n <= kWindowMin; };
+  // the offsets of the workgroup's four clusters, fetched now (lane j holds the start of cluster 4*block + j,
+  // clamped to the end) so that the sharing pass below does not start with a memory round trip
+  // (read into scalars at once: waiting for this load later, behind the row stores, would keep the wave alive
+  // until its stores have landed)
+  int32_t wg_off[5] = {0, 0, 0, 0, 0};
+  if (shares) {
+    const int32_t v = seg_offsets[min(blockIdx.x * 4u + min(lane, 4u), S)];
+#pragma unroll
+    for (int j = 0; j < 5; ++j) wg_off[j] = __builtin_amdgcn_readlane(v, j);
+  }
+  // the sharing pass comes first: after its own cluster's stores a wave should have nothing left to wait for
+  if (shares) {
+    const uint32_t s0 = blockIdx.x * 4u, w4 = threadIdx.x >> 6;
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+      const uint32_t sj = s0 + j;
+      if (sj >= S) break;  // the same for every wave of the workgroup
+      const int32_t lo = wg_off[j], hi = wg_off[j + 1];
+      const int32_t n = hi - lo;
+      if (!shared_size(n)) continue;
+      const int32_t quarter = (n + 3) / 4;
+      const int32_t a = min(lo + (int32_t)w4 * quarter, hi), b = min(a + quarter, hi);
+      float* mine = coop_sum + (size_t)w4 * cpr * E;
+      if (a < b) {
+        row_sum_kahan<DT>(tokens, perm, a, b, k, cpr, row_bytes, [&](uint32_t c, const float (&acc)[E]) {
+#pragma unroll
+          for (int i = 0; i < E; i += 4)
+            *(float4*)(mine + (size_t)c * E + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+        });
+      } else {
+        for (uint32_t i = lane; i < cpr * E; i += 64) mine[i] = 0.0f;
+      }
+      __syncthreads();
+      char* dst = centroids + (size_t)sj * row_bytes;
+      const float fn = (float)n;
+      for (uint32_t c = threadIdx.x; c < cpr; c += 256) {
+        float acc[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+          acc[i] = coop_sum[(size_t)c * E + i];
+#pragma unroll
+          for (int w = 1; w < 4; ++w) acc[i] += coop_sum[((size_t)w * cpr + c) * E + i];
+          if (mean) acc[i] /= fn;
+        }
+        store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
+      }
+      __syncthreads();  // before the partial sums are overwritten
+    }
+  }
   if (s < S) {
     const int32_t lo = uniform<LPR>(seg_offsets[s]), hi = uniform<LPR>(seg_offsets[s + 1]);
     const int32_t n = hi - lo;
-    if (LPR == 64 && n > kPlainSumMax && n <= kCentroidWindow) {
-      // a whole wave on a cluster of 17 .. kCentroidWindow members: compensated sum, eight rows in flight
+    if (shared_size(n)) {
+      // left to the workgroup, below
+    } else if (LPR == 64 && n > kPlainSumMax && n <= kWindowMin) {
+      // a whole wave on a cluster of more than 16 members: compensated sum, eight rows in flight
       char* dst = centroids + (size_t)s * row_bytes;
       const float fn = (float)n;
       row_sum_kahan<DT>(tokens, perm, lo, hi, k, cpr, row_bytes, [&](uint32_t c, float (&acc)[E]) {
@@ -180,7 +242,7 @@ __global__ __launch_bounds__(256) void centroid_kernel(
         }
         store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
       });
-    } else if (n <= kCentroidWindow) {
+    } else if (n <= kWindowMin) {
       const char* first = tokens + (size_t)((uint32_t)uniform<LPR>(perm[lo]) / k) * row_bytes;
       char* dst = centroids + (size_t)s * row_bytes;
       for (uint32_t c = lane % LPR; c < cpr; c += LPR) {
@@ -255,14 +317,14 @@ __global__ __launch_bounds__(256) void centroid_kernel(
   {
     const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[sf]);
     const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[sf + 1]);
-    if (hi - lo > kCentroidWindow)
+    if (hi - lo > kWindowMin)
       long_cluster_window<DT>(tokens, perm, seg_offsets, centroids, partial, counters, sf, (int32_t)p0,
                               min(hi, (int32_t)p1), 2 * wave, k, cpr, d, mean);
   }
   if (sl != sf) {
     const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[sl]);
     const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[sl + 1]);
-    if (hi - lo > kCentroidWindow)
+    if (hi - lo > kWindowMin)
       long_cluster_window<DT>(tokens, perm, seg_offsets, centroids, partial, counters, sl, lo, (int32_t)p1,
                               2 * wave + 1, k, cpr, d, mean);
   }
@@ -275,9 +337,11 @@ void launch_lpr(const void* tokens, const int32_t* perm, const int32_t* seg_offs
   constexpr int G = 64 / LPR;
   const uint64_t waves = ((uint64_t)N + G - 1) / G;  // worst case S == N; surplus waves leave at once
   const uint32_t blocks = (uint32_t)((waves + 3) / 4);
-  hipLaunchKernelGGL((centroid_kernel<DT, LPR>), dim3(blocks), dim3(256), 0, stream, (const char*)tokens, perm,
-                     seg_offsets, seg_of, num_segments, (char*)centroids, partial, counters, (uint32_t)N, (uint32_t)k,
-                     cpr, mean ? 1u : 0u);
+  const size_t coop_bytes = (size_t)4 * cpr * Piece<DT>::kElems * sizeof(float);  // four partial rows in binary32
+  const bool coop = LPR == 64 && coop_bytes <= kCoopMaxLds;
+  hipLaunchKernelGGL((centroid_kernel<DT, LPR>), dim3(blocks), dim3(256), coop ? coop_bytes : 0, stream,
+                     (const char*)tokens, perm, seg_offsets, seg_of, num_segments, (char*)centroids, partial, counters,
+                     (uint32_t)N, (uint32_t)k, cpr, mean ? 1u : 0u, coop ? 1u : 0u);
 }
 
 template <typename DT>
