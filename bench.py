@@ -264,6 +264,23 @@ def main():
             result["supplementary_hash_gate"] = {
                 "hash_gate_ms": float(np.mean([e0.elapsed_time(e1) for e0, e1 in evg[5:]])), "hash_ms": float(hash_ms),
                 "one_pass_over_tokens": bool(L * r + E <= 128)}
+    # context for the hash kernel: the vendor library's GEMM of the same shape (rotation only: [T, d] x [d, L*r],
+    # the rotated coordinates written out, no arg-max), timed the same way on the same rotated token copies.
+    # It is not part of the path and not part of `value`.
+    if cfg.dtype == "bf16":
+        rot2 = rot.reshape(L * r, d)
+        yrot = torch.empty((L * r, T), dtype=tdt, device="cuda")
+        evl = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(K, 50))]
+        for i, (e0, e1) in enumerate(evl):
+            e0.record()
+            torch.matmul(rot2, xs[i % copies].t(), out=yrot)
+            e1.record()
+        torch.cuda.synchronize()
+        if len(evl) > 5:
+            lib_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evl[5:]]))
+            result["hash_mfma"]["library_gemm_same_shape_ms"] = lib_ms
+            result["hash_mfma"]["library_gemm_tflops"] = hash_flops / (lib_ms * 1e-3) / 1e12
+        del yrot
     # supplementary: backward of the path (segment sums of dL/dY, then dL/dx), on random gradients
     gy = torch.randn((T, k, d), device="cuda").to(tdt)
     hc = torch.randn((N, d), device="cuda").to(tdt)
