@@ -85,6 +85,10 @@ def main():
     ap.add_argument("--sigma", type=float, default=None, help="override the within-cluster noise (supplementary runs)")
     ap.add_argument("--paper-regime-steps", type=int, default=50,
                     help="steps of the supplementary run at the paper's compression rates (0 = skip)")
+    ap.add_argument("--sweep-hashes", default="",
+                    help="comma-separated numbers of hash functions, e.g. 2,4,6,8,10: adds supplementary_hash_count_sweep "
+                         "(compression rate and step time per count, content gate, sigma 0.02)")
+    ap.add_argument("--sweep-r", type=int, default=16, help="rotated dimensions per hash function in --sweep-hashes")
     ap.add_argument("--copies", type=int, default=2, help="independent input copies rotated between steps")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -281,6 +285,37 @@ def main():
             result["hash_mfma"]["library_gemm_same_shape_ms"] = lib_ms
             result["hash_mfma"]["library_gemm_tflops"] = hash_flops / (lib_ms * 1e-3) / 1e12
         del yrot
+    # supplementary: the paper's sweep of the number of hash functions (Section 4.3), on this workload's shape with
+    # the content gate: hash lists are prefixes of one list, tokens and gate are the same for every count
+    if args.sweep_hashes:
+        counts = sorted(int(v) for v in args.sweep_hashes.split(","))
+        sr = args.sweep_r
+        scfg = synth.config(args.workload, L=counts[-1], r=sr, gate="content", sigma=0.02)
+        sw = synth.generate(scfg)
+        sx, se, srot = dev(sw.tokens), torch.from_numpy(sw.expert).cuda(), dev(sw.rot)
+        sweep = []
+        for Ls in counts:
+            rot_l = srot[:Ls].contiguous()
+            so = lsh.CompressOutputs.allocate(T, d, k, E, Ls, sr, tdt)
+
+            def sstep():
+                lsh.lshmoe_hash(sx, rot_l, bucket)
+                lsh.lshmoe_compress(sx, se, bucket, E, Ls, sr, so)
+                lsh.lshmoe_decompress(sx, so.centroids, ecs[0], so.seg_of, so.seg_offsets, k, ys[0], perm=so.perm,
+                                      num_segments=so.num_segments)
+            for _ in range(5):
+                sstep()
+            torch.cuda.synchronize()
+            ts0 = time.perf_counter()
+            for _ in range(30):
+                sstep()
+            torch.cuda.synchronize()
+            sms = (time.perf_counter() - ts0) * 1e3 / 30
+            sweep.append({"hash_functions": Ls, "compression_rate": int(so.num_segments.item()) / N, "ms_per_step": sms})
+            del so
+        result["supplementary_hash_count_sweep"] = {"workload": "%s, gate=content, sigma=0.02, r=%d" % (cfg.name, sr),
+                                                    "points": sweep}
+        del sx, se, srot
     # supplementary: backward of the path (segment sums of dL/dY, then dL/dx), on random gradients
     gy = torch.randn((T, k, d), device="cuda").to(tdt)
     hc = torch.randn((N, d), device="cuda").to(tdt)

@@ -571,6 +571,7 @@ hipError_t launch_stream(const char* x, const char* R, uint64_t* bucket, int64_t
                          hipStream_t stream, const char* gate_w = nullptr, int E = 0, float* logits = nullptr) {
   using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
   static_assert(S::kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+  if ((GATE ? L * r + E : hpg * r) > S::kRows) return hipErrorInvalidValue;  // the instance must hold every row of a pass
   auto kern = hash_stream_kernel<DT, MTW, NTW, GROUPS, HALVES, DR, DX, GATE>;
   static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
   if (!raised.load(std::memory_order_acquire)) {
@@ -588,6 +589,7 @@ template <typename DT, int MT, int NTK, int XDEPTH, int WAVES, int OCC, bool ALI
 hipError_t launch_one(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
                       hipStream_t stream) {
   constexpr int kBlockTokens = WAVES * NTK * 32;
+  if (hpg < 1 || hpg * r > MT * 32) return hipErrorInvalidValue;  // the instance must hold every row of a pass
   constexpr size_t lds_bytes = (size_t)2 * MT * 32 * kPieces * 16;
   static_assert(lds_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
   auto kern = hash_kernel<DT, MT, NTK, XDEPTH, WAVES, OCC, ALIGNED8, KTAIL>;
@@ -644,9 +646,9 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
     return LSHMOE_STREAM(4);
 #undef LSHMOE_STREAM
   }
-  if (mt >= 6) {
+  if (mt >= 5) {                           // 129..192 rows take the 6-tile instance, more the 8-tile one
     const bool wide = T >= 256 * 256;
-    if (mt == 6) return wide ? LSHMOE_HASH(6, 1, 2, 8, 1) : LSHMOE_HASH(6, 1, 2, 4, 2);
+    if (mt <= 6) return wide ? LSHMOE_HASH(6, 1, 2, 8, 1) : LSHMOE_HASH(6, 1, 2, 4, 2);
     return wide ? LSHMOE_HASH(8, 1, 2, 8, 1) : LSHMOE_HASH(8, 1, 2, 4, 2);
   }
   const int waves = T >= 512 * 128 ? 4 : T >= 512 * 64 ? 2 : 1;

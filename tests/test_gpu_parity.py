@@ -66,6 +66,29 @@ def test_content_correlated_gate_long_segments(H):
     assert run.S / cfg.N < 0.3
 
 
+def test_hash_count_sweep_refines_clusters(H):
+    # Section 4.3's sweep of the number of hash functions (2, 4, 6, 8, 10), hash lists being prefixes of one
+    # another: every L is checked against the oracle stage by stage; a further hash function only splits
+    # clusters, so S/N does not fall, and the ids of the shorter list are the longer one's with the last
+    # mixed-radix digits dropped.  L = 10 with r = 32 needs two passes over the tokens (320 rows of R).
+    r = 32
+    cfg = synth.config("gpt", T=8192 + 5, L=10, r=r, E=8, gate="content", sigma=0.05, centers=256)
+    w = synth.generate(cfg)
+    rates, prev_seg, prev_b, prev_L, prev_ties = [], None, None, None, 0
+    for L in (2, 4, 6, 8, 10):
+        print("case hash-count sweep L", L, flush=True)
+        run = H.run_and_check(w.tokens, w.rot[:L], w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
+        seg_of = run.out.seg_of.cpu().numpy().copy()
+        if prev_seg is not None and run.ties == 0 and prev_ties == 0:   # a legal near-tie flip may differ between runs
+            assert np.array_equal(run.bucket // np.uint64((2 * r) ** (L - prev_L)), prev_b)
+            pairs = np.unique(np.stack([seg_of, prev_seg], axis=1), axis=0)
+            assert len(pairs) == run.S
+        rates.append(run.S / cfg.N)
+        prev_seg, prev_b, prev_L, prev_ties = seg_of, run.bucket.copy(), L, run.ties
+    print("  S/N by L:", ["%.3f" % x for x in rates], flush=True)
+    assert rates == sorted(rates) and rates[0] < rates[-1]
+
+
 # ------------------------------------------------------------------ shapes and edge cases
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("T,d,k,E,L,r", [
@@ -199,8 +222,24 @@ def test_exact_ties_on_the_fast_hash_instance(H, dtype):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("T,L,r", [(65536 + 77, 4, 64), (65536 + 77, 2, 256), (65536 + 77, 7, 32),
+                                   (65536 + 77, 5, 32), (65536 + 77, 6, 32),
                                    (32768 + 77, 3, 32), (24576 + 3, 1, 16), (16384 + 5, 2, 32), (8192 + 1, 2, 64)])
 def test_hash_streaming_instances(H, dtype, T, L, r):
+    _hash_case(H, dtype, T, L, r)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T", [777, 8192 + 33, 24576 + 9])
+@pytest.mark.parametrize("L,r", [(1, 32), (2, 32), (3, 32), (4, 32), (5, 32), (6, 32), (7, 32), (8, 32), (10, 16),
+                                 (4, 40), (6, 24), (7, 20), (2, 88), (1, 160), (9, 32), (3, 100)])
+def test_hash_every_row_tile_count(H, dtype, T, L, r):
+    # 1..8 tiles of 32 rows per pass over the tokens (L * r rows, at most 256 per pass), at sizes that take the
+    # small, the 64-token and the 128-token workgroups; 129..160 rows (5 tiles) must take a 6-tile instance;
+    # r = 20 and r = 100 are not multiples of 8 (general epilogue), (9, 32) and (3, 100) need two passes.
+    _hash_case(H, dtype, T, L, r)
+
+
+def _hash_case(H, dtype, T, L, r):
     # Large inputs with rows of whole 128-byte chunks take the kernels that stage both operands through LDS:
     # 193..256 rows of R per pass and T >= 65536 the one that splits the rows of R between two waves and joins the
     # halves at the end (r = 256 puts ONE hash on both halves, L = 7 with r = 32 leaves the last 32 staged rows

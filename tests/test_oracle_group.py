@@ -108,3 +108,28 @@ def test_special_cases():
     # empty leading expert
     g = group_ref(np.array([[2], [2]], np.int32), np.array([1, 0], np.uint64), 3)
     assert g["expert_offsets"].tolist() == [0, 0, 0, 2]
+
+
+def test_more_hash_functions_refine_the_clusters():
+    """Section 4.3 (ablation on the number of hash functions): with the hash functions of a shorter list being a
+    prefix of a longer one, a further hash function can split a cluster but never merge two, so the cluster count
+    (and with it the compression rate S/N) does not fall; the bucket id of the shorter list is the longer one's
+    id with its last mixed-radix digits dropped (hash 0 is the most significant digit)."""
+    from oracle import hash_ref
+    from workloads import synth
+    r = 16
+    cfg = synth.config("gpt", T=3000, L=10, r=r, gate="content", sigma=0.05, centers=64)
+    w = synth.generate(cfg)
+    N = cfg.T * cfg.k
+    counts, prev_seg, prev_b, prev_L = [], None, None, None
+    for L in (2, 4, 6, 8, 10):
+        b = hash_ref(w.tokens, w.rot[:L], cfg.dtype)[0]
+        g = group_ref(w.expert, b, cfg.E)
+        counts.append(g["S"])
+        if prev_seg is not None:
+            assert np.array_equal(b // np.uint64((2 * r) ** (L - prev_L)), prev_b)
+            pairs = np.unique(np.stack([g["seg_of"], prev_seg], axis=1), axis=0)
+            assert len(pairs) == g["S"]               # every cluster lies inside exactly one cluster of the shorter list
+            assert len(np.unique(pairs[:, 1])) == len(np.unique(prev_seg))
+        prev_seg, prev_b, prev_L = g["seg_of"], b, L
+    assert counts == sorted(counts) and counts[0] < counts[-1] <= N
