@@ -72,10 +72,11 @@ def assert_rows_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str, t
 
 def run_and_check(tokens: np.ndarray, rot: np.ndarray, expert: np.ndarray, E: int, dtype: str, expert_fn,
                   flags: int = 0, use_seg_offsets: bool = True, bucket_override: np.ndarray | None = None,
-                  centroid_tol=None) -> GpuRun:
+                  centroid_tol=None, skip_hash: bool = False) -> GpuRun:
     """Run hash -> compress -> expert_fn -> decompress on the GPU and compare
     every output with the oracle.  expert_fn maps a torch [S, d] tensor of
-    centroids to the expert output (same dtype)."""
+    centroids to the expert output (same dtype).  skip_hash (with bucket_override) leaves the hash stage out:
+    for tests of the later stages at sizes where the hash oracle would dominate the run time."""
     T, d = tokens.shape
     L, r, _ = rot.shape
     k = expert.shape[1]
@@ -83,10 +84,14 @@ def run_and_check(tokens: np.ndarray, rot: np.ndarray, expert: np.ndarray, E: in
     xt, rt = to_device(tokens, dtype), to_device(rot, dtype)
     et = torch.from_numpy(np.ascontiguousarray(expert, dtype=np.int32)).cuda()
     bt = torch.empty(T, dtype=torch.int64, device="cuda")
-    lsh.lshmoe_hash(xt, rt, bt)
-    torch.cuda.synchronize()
-    bucket = bt.cpu().numpy().view(np.uint64)
-    flips, near = check_hash(bucket, tokens, rot, dtype)
+    flips = 0
+    if not skip_hash:
+        lsh.lshmoe_hash(xt, rt, bt)
+        torch.cuda.synchronize()
+        bucket = bt.cpu().numpy().view(np.uint64)
+        flips, near = check_hash(bucket, tokens, rot, dtype)
+    else:
+        assert bucket_override is not None, "skipping the hash needs bucket ids from the caller"
     if bucket_override is not None:
         bucket = np.ascontiguousarray(bucket_override, dtype=np.uint64)
         bt = torch.from_numpy(bucket.view(np.int64)).cuda()

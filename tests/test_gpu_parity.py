@@ -107,6 +107,27 @@ def test_shapes(H, dtype, T, d, k, E, L, r):
     H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn)
 
 
+@pytest.mark.parametrize("N", [4097, 32768, 32769, 70001, 131071, 131072, 300000, 524288, 524289])
+@pytest.mark.parametrize("E,L,r", [(1, 1, 2), (2, 1, 4), (3, 2, 4), (8, 1, 32), (5, 2, 16), (64, 2, 32), (9, 4, 16),
+                                   (64, 4, 64), (2, 6, 64), (100, 7, 64), (256, 8, 64)])
+def test_group_routes_by_key_width_and_size(H, N, E, L, r):
+    # The grouping step picks its route by the number of assignments and the width of the (expert, bucket) key:
+    # one workgroup up to 4096, one global pass on the top key bits plus sorts inside the bins up to 256 tiles
+    # (keys of at most 9 bits need no bin sort), radix passes beyond.  Keys from 2 bits to all 64, with bucket
+    # ids drawn from a pool a third as large as N so that clusters of several members exist at every width.
+    d, dtype = 8, "bf16"
+    rng = np.random.default_rng(N * 31 + E)
+    tokens = synth.f32_to_storage(rng.standard_normal((N, d)).astype(np.float32), dtype)
+    rot = synth.f32_to_storage(rng.standard_normal((L, r, d)).astype(np.float32), dtype)
+    expert = rng.integers(0, E, (N, 1)).astype(np.int32)
+    bits = L * int(np.log2(2 * r))
+    pool = rng.integers(0, 1 << bits, max(1, N // 3), dtype=np.uint64)
+    pool[0], pool[-1] = 0, (1 << bits) - 1                          # both ends of the id range
+    ids = pool[rng.integers(0, pool.size, N)]
+    print("case group N", N, "E", E, "bucket bits", bits, flush=True)
+    H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn, bucket_override=ids, skip_hash=True)
+
+
 def test_large_inputs_take_the_histogram_scan_scatter_route(H):
     # more than 256 sort tiles: per-pass histogram + table scan + scatter kernels
     tokens, rot, expert = _rand_inputs(41, 280000, 8, 2, 3, 2, 4, "bf16", centers=5000)
@@ -239,7 +260,16 @@ def test_hash_every_row_tile_count(H, dtype, T, L, r):
     _hash_case(H, dtype, T, L, r)
 
 
-def _hash_case(H, dtype, T, L, r):
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T", [777, 8192 + 33, 65536 + 77])
+@pytest.mark.parametrize("L,r", [(1, 32), (4, 32), (5, 32), (6, 32), (8, 32), (3, 100), (2, 256)])
+def test_hash_rows_with_a_tail(H, dtype, T, L, r):
+    # rows of 33 16-byte pieces: not a whole number of 128-byte chunks, so every size takes the general kernel
+    # with its tail step, at every number of row tiles
+    _hash_case(H, dtype, T, L, r, d=264 if dtype == "bf16" else 132)
+
+
+def _hash_case(H, dtype, T, L, r, d=None):
     # Large inputs with rows of whole 128-byte chunks take the kernels that stage both operands through LDS:
     # 193..256 rows of R per pass and T >= 65536 the one that splits the rows of R between two waves and joins the
     # halves at the end (r = 256 puts ONE hash on both halves, L = 7 with r = 32 leaves the last 32 staged rows
@@ -247,7 +277,8 @@ def _hash_case(H, dtype, T, L, r):
     # inside a lane, across lane halves, across tiles and across the two row halves, at the start and in the
     # ragged tail.
     import oracle
-    d = 256 if dtype == "bf16" else 128
+    if d is None:
+        d = 256 if dtype == "bf16" else 128
     rng = np.random.default_rng(41)
     x = rng.standard_normal((T, d)).astype(np.float32)
     rot = rng.standard_normal((L, r, d)).astype(np.float32) * 0.05
