@@ -101,6 +101,7 @@ def test_hash_count_sweep_refines_clusters(H):
     (700, 264, 1, 2, 2, 256),    # r at the supported maximum, two passes over the tokens
     (2500, 128, 2, 8, 5, 40),    # 200 rows of R in one pass, odd tile split
     (640, 72, 1, 6, 6, 8),       # the paper's default count of hash functions
+    (300, 4096, 2, 4, 2, 16),    # rows of 8 KB (bf16) / 16 KB (binary32)
 ])
 def test_shapes(H, dtype, T, d, k, E, L, r):
     tokens, rot, expert = _rand_inputs(100 + T, T, d, k, E, L, r, dtype, centers=max(2, T // 6))
@@ -152,10 +153,12 @@ def test_all_tokens_identical_one_cluster(H, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("d,k", [(64, 1), (1032, 1), (520, 2)])
+@pytest.mark.parametrize("d,k", [(64, 1), (1032, 1), (520, 2), (4096, 1)])
 def test_long_clusters_are_summed_in_windows(H, dtype, d, k):
     # cluster sizes around the window length of the centroid step (128 sorted positions) and far beyond it, with
-    # heads on and off the window grid; d = 1032 makes rows wider than one pass of a wave over the row
+    # heads on and off the window grid; d = 1032 makes rows wider than one pass of a wave over the row; with
+    # d = 4096 the four partial rows of a workgroup-shared sum no longer fit the LDS set aside for them, so
+    # clusters of 33..1024 members stay with one wave
     sizes = [128, 129, 1, 127, 256, 257, 3, 1000, 2, 5000, 131, 1, 1, 384, 640, 7, 2049]
     T, E, L, r = sum(sizes), 3, 2, 16
     tokens, rot, _ = _rand_inputs(21, T, d, 1, E, L, r, dtype)
