@@ -37,8 +37,10 @@
  *     Arguments are checked on the host before any GPU call, so the checks
  *     behave the same on a machine without a GPU.
  *   - Preconditions that are NOT checked (results are unspecified, memory
- *     safety is kept for out-of-range expert ids): finite inputs;
- *     0 <= expert[t][j] < E; the k experts of one token are distinct.
+ *     safety is kept for out-of-range expert ids, which count as E - 1, and
+ *     for bucket ids wider than (2r)^L - 1, whose extra bits are dropped): finite
+ *     inputs; 0 <= expert[t][j] < E; the k experts of one token are distinct;
+ *     bucket ids as lshmoe_hash writes them for the same L and r.
  */
 #ifndef LSHMOE_H
 #define LSHMOE_H

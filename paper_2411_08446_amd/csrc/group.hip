@@ -60,7 +60,8 @@ __device__ __forceinline__ void load_item(const KeySource& src, uint32_t i, uint
   if (FIRST) {
     uint32_t e = (uint32_t)src.expert[i];
     if (e >= src.E) e = src.E - 1;  // out-of-range ids violate the contract; stay in bounds
-    key = ((uint64_t)e << src.bbits) | src.bucket[i / src.k];
+    // bbits <= 63; ids with bits above bbits violate the contract too and must not reach the expert field
+    key = ((uint64_t)e << src.bbits) | (src.bucket[i / src.k] & ((1ull << src.bbits) - 1ull));
     idx = (int32_t)i;
   } else {
     key = src.key[i];
