@@ -28,7 +28,9 @@ __global__ __launch_bounds__(256) void grad_tokens_kernel(
   constexpr int G = 64 / LPR;
   constexpr int E = Piece<DT>::kElems;
   const uint32_t lane = threadIdx.x & 63;
-  const uint32_t t = ((blockIdx.x * 256u + threadIdx.x) >> 6) * G + lane / LPR;
+  const uint64_t wave64 = linear_block() * 4u + (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (wave64 * G >= T) return;
+  const uint32_t t = (uint32_t)(wave64 * G) + lane / LPR;   // below T + 64: 32 bits are enough
   if (t >= T) return;
   const size_t row_bytes = (size_t)cpr * 16;
   const bool no_res = (flags & 1u) != 0;
@@ -69,7 +71,7 @@ void launch_lpr(const void* grad_out, const void* grad_centroids, const void* gr
   constexpr int G = 64 / LPR;
   const uint64_t waves = ((uint64_t)T + G - 1) / G;
   const uint32_t blocks = (uint32_t)((waves + 3) / 4);
-  hipLaunchKernelGGL((grad_tokens_kernel<DT, LPR>), dim3(blocks), dim3(256), 0, stream, (const char*)grad_out,
+  hipLaunchKernelGGL((grad_tokens_kernel<DT, LPR>), grid_of_blocks(blocks), dim3(256), 0, stream, (const char*)grad_out,
                      (const char*)grad_centroids, (const char*)grad_expert_out, seg_of, seg_offsets,
                      (char*)grad_tokens, (uint32_t)T, (uint32_t)k, cpr, flags);
 }

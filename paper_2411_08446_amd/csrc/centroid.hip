@@ -168,7 +168,10 @@ __global__ __launch_bounds__(256) void centroid_kernel(
   extern __shared__ float coop_sum[];  // coop: [4 waves][cpr * E] partial sums of a cluster the workgroup shares
   const uint32_t S = (uint32_t)*num_segments;
   const uint32_t lane = threadIdx.x & 63;
-  const uint32_t wave = (blockIdx.x * 256u + threadIdx.x) >> 6;
+  const uint64_t block64 = linear_block();
+  if (block64 * 4u > (uint64_t)N) return;   // surplus workgroups of a folded grid (whole workgroup: no barrier is skipped by part of one)
+  const uint32_t block = (uint32_t)block64;
+  const uint32_t wave = block * 4u + (threadIdx.x >> 6);
   const uint32_t s = wave * G + lane / LPR;
   const size_t row_bytes = (size_t)cpr * 16;
   // Clusters of kCoopMin+1 .. kWindowMin members (whole-wave rows only): a single wave walking such a
@@ -183,13 +186,13 @@ __global__ __launch_bounds__(256) void centroid_kernel(
   // until its stores have landed)
   int32_t wg_off[5] = {0, 0, 0, 0, 0};
   if (shares) {
-    const int32_t v = seg_offsets[min(blockIdx.x * 4u + min(lane, 4u), S)];
+    const int32_t v = seg_offsets[min(block * 4u + min(lane, 4u), S)];
 #pragma unroll
     for (int j = 0; j < 5; ++j) wg_off[j] = __builtin_amdgcn_readlane(v, j);
   }
   // the sharing pass comes first: after its own cluster's stores a wave should have nothing left to wait for
   if (shares) {
-    const uint32_t s0 = blockIdx.x * 4u, w4 = threadIdx.x >> 6;
+    const uint32_t s0 = block * 4u, w4 = threadIdx.x >> 6;
 #pragma unroll
     for (uint32_t j = 0; j < 4; ++j) {
       const uint32_t sj = s0 + j;
@@ -339,7 +342,7 @@ void launch_lpr(const void* tokens, const int32_t* perm, const int32_t* seg_offs
   const uint32_t blocks = (uint32_t)((waves + 3) / 4);
   const size_t coop_bytes = (size_t)4 * cpr * Piece<DT>::kElems * sizeof(float);  // four partial rows in binary32
   const bool coop = LPR == 64 && coop_bytes <= kCoopMaxLds;
-  hipLaunchKernelGGL((centroid_kernel<DT, LPR>), dim3(blocks), dim3(256), coop ? coop_bytes : 0, stream,
+  hipLaunchKernelGGL((centroid_kernel<DT, LPR>), grid_of_blocks(blocks), dim3(256), coop ? coop_bytes : 0, stream,
                      (const char*)tokens, perm, seg_offsets, seg_of, num_segments, (char*)centroids, partial, counters,
                      (uint32_t)N, (uint32_t)k, cpr, mean ? 1u : 0u, coop ? 1u : 0u);
 }

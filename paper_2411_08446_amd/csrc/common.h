@@ -22,6 +22,17 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   return u >> 16;
 }
 
+// One wave per row (or cluster) can mean more than 2^32 threads, which a one-dimensional launch cannot express
+// (a dispatch counts work-items per dimension in 32 bits): grids of 256-thread workgroups beyond 2^22 workgroups
+// are folded into two dimensions.  Surplus workgroups of the last row leave through the kernels' bounds checks.
+inline dim3 grid_of_blocks(uint64_t blocks) {
+  constexpr uint64_t kMaxX = 1ull << 22;
+  if (blocks <= kMaxX) return dim3((uint32_t)(blocks == 0 ? 1 : blocks));
+  const uint64_t by = (blocks + kMaxX - 1) / kMaxX;
+  return dim3((uint32_t)((blocks + by - 1) / by), (uint32_t)by);
+}
+__device__ __forceinline__ uint64_t linear_block() { return (uint64_t)blockIdx.y * gridDim.x + blockIdx.x; }
+
 // Rows are moved as raw 16-byte pieces (uint4) and only widened to binary32
 // where arithmetic happens, so that loads in flight cost 4 registers each.
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));

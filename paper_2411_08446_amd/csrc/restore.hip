@@ -36,7 +36,13 @@ __global__ __launch_bounds__(256) void restore_kernel(
   constexpr int G = 64 / LPR;
   constexpr int E = Piece<DT>::kElems;
   const uint32_t lane = threadIdx.x & 63;
-  const uint32_t a0 = (((blockIdx.x * 256u + threadIdx.x) >> 6) * G + lane / LPR) * kRows;
+  // a folded grid can pass 2^32 threads: the workgroup's first row is checked in 64 bits, the rest fits 32.
+  // The row index is left in a vector register on purpose: with a scalar index the cluster lookups below
+  // become scalar-cache loads, and this kernel then runs 3 us slower at the T5 shape (the gate-weighted
+  // variant and the token-gradient kernel, which have one more lookup per row, gain from the scalar form).
+  const uint64_t block64 = linear_block();
+  if (block64 * (4u * G * kRows) >= N) return;
+  const uint32_t a0 = (((uint32_t)block64 * 4u + (threadIdx.x >> 6)) * G + lane / LPR) * kRows;
   if (a0 >= N) return;
   const size_t row_bytes = (size_t)cpr * 16;
   const bool no_res = (flags & 1u) != 0;
@@ -106,7 +112,9 @@ __global__ __launch_bounds__(256) void restore_combine_kernel(
   constexpr int G = 64 / LPR;
   constexpr int E = Piece<DT>::kElems;
   const uint32_t lane = threadIdx.x & 63;
-  const uint32_t t = ((blockIdx.x * 256u + threadIdx.x) >> 6) * G + lane / LPR;
+  const uint64_t wave64 = linear_block() * 4u + (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (wave64 * G >= T) return;
+  const uint32_t t = (uint32_t)(wave64 * G) + lane / LPR;   // below T + 64: 32 bits are enough
   if (t >= T) return;
   const size_t row_bytes = (size_t)cpr * 16;
   const bool no_res = (flags & 1u) != 0;
@@ -147,7 +155,7 @@ void launch_combine_lpr(const void* tokens, const void* centroids, const void* e
   constexpr int G = 64 / LPR;
   const uint64_t waves = ((uint64_t)T + G - 1) / G;
   const uint32_t blocks = (uint32_t)((waves + 3) / 4);
-  hipLaunchKernelGGL((restore_combine_kernel<DT, LPR>), dim3(blocks), dim3(256), 0, stream, (const char*)tokens,
+  hipLaunchKernelGGL((restore_combine_kernel<DT, LPR>), grid_of_blocks(blocks), dim3(256), 0, stream, (const char*)tokens,
                      (const char*)centroids, (const char*)expert_out, seg_of, seg_offsets, gate_weight, (char*)out,
                      (uint32_t)T, (uint32_t)k, cpr, flags);
 }
@@ -172,7 +180,7 @@ void launch_lpr(const void* tokens, const void* centroids, const void* expert_ou
   const uint64_t groups = ((uint64_t)N + kRows - 1) / kRows;
   const uint64_t waves = (groups + G - 1) / G;
   const uint32_t blocks = (uint32_t)((waves + 3) / 4);
-  hipLaunchKernelGGL((restore_kernel<DT, LPR>), dim3(blocks), dim3(256), 0, stream, (const char*)tokens,
+  hipLaunchKernelGGL((restore_kernel<DT, LPR>), grid_of_blocks(blocks), dim3(256), 0, stream, (const char*)tokens,
                      (const char*)centroids, (const char*)expert_out, seg_of, seg_offsets, perm, num_segments,
                      (char*)out, (uint32_t)N, (uint32_t)k, cpr, flags);
 }

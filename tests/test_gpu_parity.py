@@ -499,3 +499,120 @@ def test_outputs_do_not_overrun(H):
     assert torch.all(cent[N:] == 7.0)
     S = int(sub.num_segments.item())
     assert torch.all(cent[S:N] == 7.0)       # rows past S are left alone
+
+
+def test_maximum_size_indexing(H):
+    # 2^27 + 6 assignments (T = 2^26 + 3 tokens, k = 2) of 272-byte rows: the centroid step then starts more than
+    # 2^26 waves and the restore step more than 2^27 rows, where a 32-bit thread index would wrap.  The oracle
+    # cannot run at this size: clusters are built so that every output has a closed form (tokens 2m and 2m + 1
+    # share bucket m and both go to experts 2(m mod 2) and 2(m mod 2) + 1), which torch evaluates on the device
+    # with the path's own arithmetic (binary32 sum of two rows, halved, rounded once; e + (x - c) rounded once),
+    # and sampled tokens, clusters and rows are compared with the oracle.
+    import oracle
+    dtype, tdt = "bf16", torch.bfloat16
+    T, d, k, E, L, r = (1 << 26) + 3, 136, 2, 4, 6, 16
+    N, M = T * k, (T + 1) // 2
+    dev = "cuda"
+    print("case maximum size T", T, "N", N, flush=True)
+    g = torch.Generator(device=dev)
+    g.manual_seed(77)
+    xt = torch.empty((T, d), dtype=tdt, device=dev)
+    step = 1 << 22
+    for lo in range(0, T, step):
+        hi = min(T, lo + step)
+        xt[lo:hi] = torch.randn((hi - lo, d), generator=g, device=dev).to(tdt)
+    rot_np = synth.f32_to_storage(np.random.default_rng(5).standard_normal((L, r, d)).astype(np.float32), dtype)
+    rt = H.to_device(rot_np, dtype)
+    tt = torch.arange(T, device=dev, dtype=torch.int64)
+    m_of_t = tt // 2
+    et = torch.stack([(m_of_t % 2) * 2, (m_of_t % 2) * 2 + 1], dim=1).to(torch.int32).contiguous()
+
+    # hash at full size, checked on a sample
+    bt = torch.empty(T, dtype=torch.int64, device=dev)
+    H.lsh.lshmoe_hash(xt, rt, bt)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    samp = np.unique(np.concatenate([rng.integers(0, T, 4000), [0, 1, T - 2, T - 1, (1 << 26) - 1, 1 << 26]]))
+    st = torch.from_numpy(samp).to(dev)
+    H.check_hash(bt[st].cpu().numpy().view(np.uint64), H.to_storage(xt[st], dtype), rot_np, dtype)
+    print("  hash sample ok", flush=True)
+
+    out = H.lsh.CompressOutputs.allocate(T, d, k, E, L, r, tdt)
+    H.lsh.lshmoe_compress(xt, et, m_of_t, E, L, r, out)
+    torch.cuda.synchronize()
+    S = int(out.num_segments.item())
+    assert S == 2 * M
+    # expected order: experts 0, 1 hold the even m (slot j = 0, 1), experts 2, 3 the odd m
+    perm_parts, size_parts = [], []
+    for e in range(E):
+        j, par = e % 2, e // 2
+        ms = torch.arange(par, M, 2, device=dev, dtype=torch.int64)
+        a0, a1 = (2 * ms) * k + j, (2 * ms + 1) * k + j
+        both = torch.stack([a0, a1], dim=1).reshape(-1)
+        keep = torch.stack([2 * ms < T, 2 * ms + 1 < T], dim=1).reshape(-1)
+        perm_parts.append(both[keep])
+        size_parts.append((2 * ms + 1 < T).to(torch.int64) + 1)
+    perm_ref = torch.cat(perm_parts)
+    sizes = torch.cat(size_parts)
+    offs_ref = torch.zeros(S + 1, dtype=torch.int64, device=dev)
+    offs_ref[1:] = torch.cumsum(sizes, 0)
+    assert perm_ref.numel() == N and int(offs_ref[-1]) == N
+    assert torch.equal(out.perm.to(torch.int64), perm_ref)
+    assert torch.equal(out.seg_offsets[:S + 1].to(torch.int64), offs_ref)
+    seg_ref = torch.empty(N, dtype=torch.int64, device=dev)
+    seg_ref[perm_ref] = torch.repeat_interleave(torch.arange(S, device=dev), sizes)
+    assert torch.equal(out.seg_of.to(torch.int64), seg_ref)
+    eoff = [0]
+    for part in size_parts:
+        eoff.append(eoff[-1] + part.numel())
+    assert out.expert_offsets.cpu().tolist() == eoff
+    assert torch.equal(out.seg_expert[:S].to(torch.int64),
+                       torch.repeat_interleave(torch.arange(E, device=dev), torch.tensor([p.numel() for p in size_parts], device=dev)))
+    del seg_ref, perm_parts, size_parts
+    print("  grouping ok, S", S, flush=True)
+
+    # centroids: (x0 + x1) / 2 in binary32, rounded once; one-member clusters copy their token
+    first = perm_ref[offs_ref[:-1]] // k
+    second = perm_ref[torch.clamp(offs_ref[:-1] + 1, max=N - 1)] // k
+    two = sizes == 2
+    cstep = 1 << 22
+    for lo in range(0, S, cstep):
+        hi = min(S, lo + cstep)
+        x0, x1 = xt[first[lo:hi]].float(), xt[second[lo:hi]].float()
+        ref = torch.where(two[lo:hi, None], (x0 + x1) / 2.0, x0).to(tdt)
+        assert torch.equal(out.centroids[lo:hi].view(torch.int16), ref.view(torch.int16)), "centroid rows %d.." % lo
+    del first, second
+    print("  centroids ok", flush=True)
+    cs = np.unique(np.concatenate([rng.integers(0, S, 1500), [0, 1, S - 2, S - 1, S // 2]]))
+    for s in cs[:: max(1, len(cs) // 300)]:   # the oracle on a few hundred clusters, one at a time
+        lo, hi = int(offs_ref[s]), int(offs_ref[s + 1])
+        rows = H.to_storage(xt[perm_ref[lo:hi] // k], dtype)
+        c_ref = oracle.centroid_ref(rows, np.arange(hi - lo, dtype=np.int32), np.array([0, hi - lo], np.int32), 1, dtype)
+        H.assert_rows_close(H.to_storage(out.centroids[s:s + 1], dtype), c_ref, dtype, "centroid %d" % s)
+
+    ect = torch.empty((S, d), dtype=tdt, device=dev)
+    for lo in range(0, S, cstep):
+        hi = min(S, lo + cstep)
+        ect[lo:hi] = _scale_fn(out.centroids[lo:hi])
+    y1 = torch.empty((T, k, d), dtype=tdt, device=dev)
+    y2 = torch.empty((T, k, d), dtype=tdt, device=dev)
+    H.lsh.lshmoe_decompress(xt, out.centroids, ect, out.seg_of, out.seg_offsets, k, y1)
+    H.lsh.lshmoe_decompress(xt, out.centroids, ect, out.seg_of, out.seg_offsets, k, y2, perm=out.perm,
+                            num_segments=out.num_segments)
+    torch.cuda.synchronize()
+    y1f, y2f = y1.view(N, d), y2.view(N, d)
+    astep = 1 << 22
+    for lo in range(0, N, astep):
+        hi = min(N, lo + astep)
+        s_a = out.seg_of[lo:hi].to(torch.int64)
+        t_a = torch.arange(lo, hi, device=dev) // k
+        ref = (ect[s_a].float() + (xt[t_a].float() - out.centroids[s_a].float())).to(tdt)
+        assert torch.equal(y1f[lo:hi].view(torch.int16), ref.view(torch.int16)), "restored rows %d.." % lo
+        assert torch.equal(y2f[lo:hi].view(torch.int16), ref.view(torch.int16)), "restored rows (cluster order) %d.." % lo
+    print("  restore ok", flush=True)
+    asamp = np.unique(np.concatenate([rng.integers(0, N, 3000), [0, 1, N - 2, N - 1, (1 << 27) - 1, 1 << 27]]))
+    at = torch.from_numpy(asamp).to(dev)
+    s_a = out.seg_of[at].to(torch.int64)
+    y_ref = oracle.restore_ref(H.to_storage(xt[at // k], dtype), H.to_storage(out.centroids[s_a], dtype),
+                               H.to_storage(ect[s_a], dtype), np.arange(len(asamp), dtype=np.int32), 1, dtype)
+    H.assert_rows_close(H.to_storage(y1f[at], dtype), y_ref, dtype, "restore sample")
