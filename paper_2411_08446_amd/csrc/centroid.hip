@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void centroid_kernel(
   const uint64_t block64 = linear_block();
   if (block64 * 4u > (uint64_t)N) return;   // surplus workgroups of a folded grid (whole workgroup: no barrier is skipped by part of one)
   const uint32_t block = (uint32_t)block64;
-  const uint32_t wave = block * 4u + (threadIdx.x >> 6);
+  const uint32_t wave = block * 4u + (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t s = wave * G + lane / LPR;
   const size_t row_bytes = (size_t)cpr * 16;
   // Clusters of kCoopMin+1 .. kWindowMin members (whole-wave rows only): a single wave walking such a
