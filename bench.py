@@ -337,7 +337,11 @@ def main():
         gtok_ms = float(np.mean([e1.elapsed_time(e2) for _, e1, e2 in evb[5:]]))
         seg_bytes = (N + S) * row + 4 * N + 4 * (S + 1)                       # N gradient rows read, S sums written
         gtok_bytes = (S + T + n_multi_assign + n_multi_seg) * row + 4 * N + 4 * (S + 1)
+        # the two calls run back to back as in a backward pass (the second finds part of the gradient rows the
+        # first has just read in the last-level cache); the event between them splits the pair's time only
+        # roughly - the kernel trace under profiles/ has the per-kernel durations
         result["supplementary_backward"] = {
+            "pair_ms": float(np.mean([e0.elapsed_time(e2) for e0, _, e2 in evb[5:]])),
             "decompress_backward_ms": seg_ms, "decompress_backward_gbs": seg_bytes / (seg_ms * 1e-3) / 1e9,
             "compress_backward_ms": gtok_ms, "compress_backward_gbs": gtok_bytes / (gtok_ms * 1e-3) / 1e9}
     if args.cpu_sample > 0:
