@@ -56,6 +56,9 @@ def test_named_configs_full_size(H, name):
     print("case", cfg.name, "full size T", cfg.T, flush=True)
     run = H.run_and_check(w.tokens, w.rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed))
     print("  S/N %.3f  tie flips %d" % (run.S / cfg.N, run.ties), flush=True)
+    # the fused gate-weighted combine and the backward pair at the same size, on the clusters of this run
+    H.check_combine(run, w.tokens, w.gate_weight, cfg.k, cfg.dtype)
+    H.check_backward(run, cfg.T, cfg.d, cfg.k, cfg.dtype, seed=w.seed + 17)
 
 
 def test_content_correlated_gate_long_segments(H):
