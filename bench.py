@@ -74,6 +74,47 @@ def cpu_baseline(w, sample_tokens: int):
 EVENT_EVERY = 8   # steps between two steps whose stages are timed with events
 
 
+def measured_peaks():
+    """What this GPU sustains, from the small probe library built beside the main one: a streaming read and a
+    streaming copy of 2 GiB (far beyond the 256 MB last-level cache) and a loop of independent bf16 MFMAs.
+    Best of 5 runs each, timed with events on the current stream."""
+    import ctypes
+    import torch
+    from paper_2411_08446_amd import build as lsh_build
+    lib = ctypes.CDLL(lsh_build.PEAKS_LIB_PATH)
+    lib.peaks_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    lib.peaks_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    lib.peaks_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    stream = torch.cuda.current_stream().cuda_stream
+    nbytes = 2 << 30
+    src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    blocks, iters = 4096, 1000
+    mout = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+
+    def best(fn):
+        times = []
+        for _ in range(6):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            rc = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            if rc != 0:
+                raise RuntimeError("peak probe failed with HIP error %d" % rc)
+            times.append(e0.elapsed_time(e1))
+        return min(times[1:])
+
+    t_read = best(lambda: lib.peaks_read(src.data_ptr(), nbytes, sink.data_ptr(), 8192, stream))
+    t_copy = best(lambda: lib.peaks_copy(src.data_ptr(), dst.data_ptr(), nbytes, 8192, stream))
+    t_mfma = best(lambda: lib.peaks_mfma_bf16(blocks, iters, mout.data_ptr(), stream))
+    return {"hbm_read_gbs": nbytes / (t_read * 1e-3) / 1e9,
+            "hbm_copy_gbs": 2 * nbytes / (t_copy * 1e-3) / 1e9,      # bytes read plus bytes written
+            "mfma_bf16_tflops": blocks * 4 * iters * 4 * 32768 / (t_mfma * 1e-3) / 1e12,
+            "note": "2 GiB streaming read / copy (read + written bytes) by 8192 workgroups, %d x 4 waves x %d x 4 MFMA 32x32x16 bf16" % (blocks, iters)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +130,9 @@ def main():
                     help="comma-separated numbers of hash functions, e.g. 2,4,6,8,10: adds supplementary_hash_count_sweep "
                          "(compression rate and step time per count, content gate, sigma 0.02)")
     ap.add_argument("--sweep-r", type=int, default=16, help="rotated dimensions per hash function in --sweep-hashes")
+    ap.add_argument("--peaks", action="store_true",
+                    help="also measure what this GPU sustains (streaming read, streaming copy, bf16 MFMA loop) and "
+                         "add measured_peaks to the line")
     ap.add_argument("--copies", type=int, default=2, help="independent input copies rotated between steps")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -344,6 +388,11 @@ def main():
             "pair_ms": float(np.mean([e0.elapsed_time(e2) for e0, _, e2 in evb[5:]])),
             "decompress_backward_ms": seg_ms, "decompress_backward_gbs": seg_bytes / (seg_ms * 1e-3) / 1e9,
             "compress_backward_ms": gtok_ms, "compress_backward_gbs": gtok_bytes / (gtok_ms * 1e-3) / 1e9}
+    if args.peaks:
+        result["measured_peaks"] = measured_peaks()
+        result["roofline"]["frac_of_measured_copy_rate"] = (
+            MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.gate), restore_bytes) / (dec_ms * 1e-3) / 1e9
+            / result["measured_peaks"]["hbm_copy_gbs"])
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample)
     else:

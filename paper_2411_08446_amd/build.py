@@ -17,6 +17,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "liblshmoe.so")
+PEAKS_LIB_PATH = os.path.join(LIB_DIR, "libpeaks.so")   # measured-peak probes of bench.py --peaks, not part of the path
 BUILD_DIR = os.path.join(ROOT, "_build")
 
 SOURCES = ["api.hip", "hash.hip", "group.hip", "centroid.hip", "restore.hip", "backward.hip"]
@@ -52,8 +53,13 @@ def build(verbose: bool = True) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed: %s\n%s\n%s" % (" ".join(cmd), res.stdout, res.stderr))
+    peaks_obj = _compile("peaks.hip")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", peaks_obj, "-o", PEAKS_LIB_PATH]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link failed: %s\n%s\n%s" % (" ".join(cmd), res.stdout, res.stderr))
     if verbose:
-        print("built", LIB_PATH)
+        print("built", LIB_PATH, "and", PEAKS_LIB_PATH)
     return LIB_PATH
 
 

@@ -15,8 +15,8 @@ HEADER = os.path.join(ROOT, "include", "lshmoe.h")
 
 @pytest.fixture(scope="module")
 def lib():
-    if not os.path.exists(lsh.LIB_PATH):
-        from paper_2411_08446_amd import build
+    from paper_2411_08446_amd import build
+    if not os.path.exists(lsh.LIB_PATH) or not os.path.exists(build.PEAKS_LIB_PATH):
         build.build(verbose=False)
     return lsh.load_library()
 
@@ -34,6 +34,17 @@ def test_header_symbols_are_exported(lib):
             "lshmoe_status_string", "lshmoe_last_error", "lshmoe_abi_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
+
+
+def test_probe_library_loads_and_exports(lib):
+    # the measured-peak probes of bench.py --peaks live in a library of their own, built by the same build step
+    from paper_2411_08446_amd import build
+    assert os.path.exists(build.PEAKS_LIB_PATH)
+    probes = ctypes.CDLL(build.PEAKS_LIB_PATH)
+    for n in ("peaks_read", "peaks_copy", "peaks_mfma_bf16"):
+        assert hasattr(probes, n), n
+    probes.peaks_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    assert probes.peaks_read(None, 16, None, 1, None) != 0          # rejected before any GPU call
 
 
 def test_status_strings(lib):
