@@ -382,7 +382,9 @@ def test_backward_long_clusters(H, dtype):
                                      (9000, 1, 8, 5),           # E not a multiple of 4, a single tile
                                      (70000, 4, 64, 64),        # T5 shape: hash as usual, then the gate rows alone
                                      (100, 2, 16, 128),         # tiny T, widest gate
-                                     (5000, 12, 8, 30)])        # 96 + 30 rows
+                                     (5000, 12, 8, 30),         # 96 + 30 rows
+                                     (20000, 6, 16, 1),         # a single gate row: a logit can cancel to almost nothing
+                                     (24576, 10, 32, 2)])       # 320 hash rows (two passes), two gate rows
 def test_hash_gate(H, dtype, T, L, r, E):
     import oracle
     d = 256 if dtype == "bf16" else 128
@@ -404,8 +406,16 @@ def test_hash_gate(H, dtype, T, L, r, E):
     assert np.array_equal(plain.cpu().numpy().view(np.uint64), bucket)
     ref = oracle.gate_logits_ref(tokens, gate, dtype)
     got = lt[:T].cpu().numpy().astype(np.float64)
-    err = oracle.row_rel_err(got, ref)
-    assert err.max() <= 1e-5, "gate logits: row %d off by %.3g" % (int(err.argmax()), err.max())
+    # binary32 accumulation of d exact-or-binary32 products, 16 per MFMA: |error| <= (d/16 + 8) 2^-24 sum_i |x_i w_i|.
+    # (Scaling by the row's largest logit, as for the other outputs, is not meaningful here: with one or two gate
+    # rows every logit of a token can cancel to almost nothing.)
+    xa, wa = np.abs(oracle.widen(tokens, dtype)), np.abs(oracle.widen(gate, dtype))
+    bound = (d / 16 + 8) * 2.0 ** -24 * (xa @ wa.T)
+    worst = np.max(np.abs(got - ref) - bound)
+    assert worst <= 0.0, "gate logits off by %.3g beyond the accumulation bound" % worst
+    if E >= 16:
+        err = oracle.row_rel_err(got, ref)
+        assert err.max() <= 1e-5, "gate logits: row %d off by %.3g" % (int(err.argmax()), err.max())
 
 
 def test_path_replays_from_a_graph(H):
