@@ -7,9 +7,11 @@
 // the row; with rows of 1 KB and more that is a whole wave per cluster, and
 // the cluster's offsets and member ids are wave-uniform scalars.  A one-member
 // cluster is a plain row copy.  Centroid rows are written with streaming
-// stores: nothing in this kernel reads them again.  A cluster with more than
-// kCentroidWindow members is cut into windows that many waves sum side by
-// side; the wave that finishes last adds the window sums in position order.
+// stores: nothing in this kernel reads them again.  By size: up to 16 members a
+// plain sum, up to 32 a compensated one, up to kWindowMin the four waves of
+// the workgroup share the cluster through LDS, beyond that the cluster is cut
+// into blocks of positions that many workgroups (or waves) sum side by side;
+// the one that finishes last adds the block sums in position order.
 #include "kernels.h"
 
 namespace lshmoe {
@@ -156,6 +158,101 @@ __device__ __forceinline__ void long_cluster_window(
     }
     store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
   }
+}
+
+
+// The same with the four waves of a workgroup on one block of 4 * kCentroidWindow positions (needs the LDS of the
+// shared sums): every wave sums its quarter of the block's part of the cluster into LDS, wave 0 adds the four in
+// wave order, writes ONE partial row and bumps the counter - a quarter of the device-scope fences, which are
+// what a very long cluster pays for.  The last workgroup's wave 0 adds the partial rows in position order.
+// Called by all four waves of the workgroup with the same arguments (two barriers inside).
+constexpr uint32_t kWgWindow = 4 * kCentroidWindow;
+
+template <typename DT>
+__device__ __forceinline__ void long_cluster_wg_window(
+    const char* __restrict__ tokens, const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_offsets,
+    char* __restrict__ centroids, float* partial, uint32_t* counters, float* coop_sum, int32_t s, uint32_t block_p0,
+    int32_t a, int32_t b, uint32_t slot, uint32_t k, uint32_t cpr, uint32_t d, uint32_t mean) {
+  constexpr int E = Piece<DT>::kElems;
+  const size_t row_bytes = (size_t)cpr * 16;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t w4 = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int32_t qa = max(a, (int32_t)(block_p0 + w4 * kCentroidWindow));
+  const int32_t qb = min(b, (int32_t)(block_p0 + (w4 + 1) * kCentroidWindow));
+  float* mine = coop_sum + (size_t)w4 * d;
+  if (qa < qb) {
+    row_sum_kahan<DT>(tokens, perm, qa, qb, k, cpr, row_bytes, [&](uint32_t c, const float (&acc)[E]) {
+#pragma unroll
+      for (int i = 0; i < E; i += 4)
+        *(float4*)(mine + (size_t)c * E + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+    });
+  } else {
+    for (uint32_t i = lane; i < d; i += 64) mine[i] = 0.0f;
+  }
+  __syncthreads();
+  if (w4 == 0) {
+    float* out_row = partial + (size_t)slot * d;
+    for (uint32_t i = lane * 4; i < d; i += 256) {   // d is a multiple of 4
+      float4 v = *(const float4*)(coop_sum + i);
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const float4 u = *(const float4*)(coop_sum + (size_t)w * d + i);
+        v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+      }
+      *(float4*)(out_row + i) = v;
+    }
+    const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[s]);
+    const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[s + 1]);
+    const uint32_t m0 = (uint32_t)lo / kWgWindow, m1 = (uint32_t)(hi - 1) / kWgWindow;
+    const uint32_t first_slot = 2 * m0 + ((uint32_t)lo % kWgWindow != 0 ? 1u : 0u);
+    __threadfence();  // the partial row is visible device-wide before the counter moves
+    uint32_t old = 0;
+    if (lane == 0) old = atomicAdd(&counters[first_slot], 1u);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if (old == m1 - m0) {
+      __threadfence();  // last block of the cluster: every other partial row is complete and visible
+      const uint32_t nwin = m1 - m0 + 1;
+      const float fn = (float)(hi - lo);
+      char* dst = centroids + (size_t)s * row_bytes;
+      constexpr int kRows = 4;
+      for (uint32_t c = lane; c < cpr; c += 64) {
+        float acc[E], comp[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = comp[i] = 0.0f;
+        for (uint32_t j = 0; j < nwin; j += kRows) {
+          float x[kRows][E];
+#pragma unroll
+          for (int u = 0; u < kRows; ++u) {
+            const uint32_t jj = min(j + u, nwin - 1);
+            const float* src = partial + (size_t)(jj == 0 ? first_slot : 2 * (m0 + jj)) * d + (size_t)c * E;
+#pragma unroll
+            for (int i = 0; i < E; i += 4) {
+              const float4 v = *(const float4*)(src + i);
+              x[u][i] = v.x; x[u][i + 1] = v.y; x[u][i + 2] = v.z; x[u][i + 3] = v.w;
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < kRows; ++u) {
+            if (j + u < nwin) {
+#pragma unroll
+              for (int i = 0; i < E; ++i) {
+                const float y = x[u][i] - comp[i];
+                const float t = acc[i] + y;
+                comp[i] = (t - acc[i]) - y;
+                acc[i] = t;
+              }
+            }
+          }
+        }
+        if (mean) {
+#pragma unroll
+          for (int i = 0; i < E; ++i) acc[i] /= fn;
+        }
+        store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
+      }
+    }
+  }
+  __syncthreads();  // before the LDS rows are used again
 }
 
 template <typename DT, int LPR>
@@ -309,6 +406,30 @@ __global__ __launch_bounds__(256) void centroid_kernel(
         store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
       }
     }
+  }
+  if (shares) {
+    // window duty with the workgroup's LDS rows: workgroup m looks after block m of 4 * kCentroidWindow positions
+    // (every wave of the workgroup gets here: nothing above returns for a single wave)
+    if ((uint64_t)block * kWgWindow >= N) return;
+    const uint32_t p0 = block * kWgWindow, p1 = min(p0 + kWgWindow, N);
+    const uint32_t d = cpr * E;
+    const int32_t sf = __builtin_amdgcn_readfirstlane(seg_of[perm[p0]]);
+    const int32_t sl = __builtin_amdgcn_readfirstlane(seg_of[perm[p1 - 1]]);
+    {
+      const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[sf]);
+      const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[sf + 1]);
+      if (hi - lo > kWindowMin)
+        long_cluster_wg_window<DT>(tokens, perm, seg_offsets, centroids, partial, counters, coop_sum, sf, p0, (int32_t)p0,
+                                   min(hi, (int32_t)p1), 2 * block, k, cpr, d, mean);
+    }
+    if (sl != sf) {
+      const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[sl]);
+      const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[sl + 1]);
+      if (hi - lo > kWindowMin)
+        long_cluster_wg_window<DT>(tokens, perm, seg_offsets, centroids, partial, counters, coop_sum, sl, p0, lo,
+                                   (int32_t)p1, 2 * block + 1, k, cpr, d, mean);
+    }
+    return;
   }
   // window duty: wave m looks after block m of the sorted positions
   if ((uint64_t)wave * kCentroidWindow >= N) return;
