@@ -161,12 +161,14 @@ __device__ __forceinline__ void long_cluster_window(
 }
 
 
-// The same with the four waves of a workgroup on one block of 4 * kCentroidWindow positions (needs the LDS of the
-// shared sums): every wave sums its quarter of the block's part of the cluster into LDS, wave 0 adds the four in
-// wave order, writes ONE partial row and bumps the counter - a quarter of the device-scope fences, which are
-// what a very long cluster pays for.  The last workgroup's wave 0 adds the partial rows in position order.
-// Called by all four waves of the workgroup with the same arguments (two barriers inside).
+// The same with the four waves of a workgroup on one block of kWgWindow positions (needs the LDS of the shared
+// sums): every wave sums its quarter of the block's part of the cluster into LDS, wave 0 adds the four in wave
+// order, writes ONE partial row and bumps the counter - a quarter of the device-scope fences.  The workgroup that
+// brings the counter to the cluster's block count adds the partial rows in position order, again a quarter per
+// wave joined through LDS in wave order, so the result does not depend on which workgroup came last.
+// Called by all four waves of the workgroup with the same arguments (barriers inside).
 constexpr uint32_t kWgWindow = 4 * kCentroidWindow;
+static_assert(kWgWindow <= (uint32_t)kWindowMin, "a block meets at most two clusters that are cut into blocks");
 
 template <typename DT>
 __device__ __forceinline__ void long_cluster_wg_window(
@@ -177,8 +179,9 @@ __device__ __forceinline__ void long_cluster_wg_window(
   const size_t row_bytes = (size_t)cpr * 16;
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t w4 = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int32_t qa = max(a, (int32_t)(block_p0 + w4 * kCentroidWindow));
-  const int32_t qb = min(b, (int32_t)(block_p0 + (w4 + 1) * kCentroidWindow));
+  uint32_t* last_flag = reinterpret_cast<uint32_t*>(coop_sum + (size_t)4 * d);   // one word behind the four rows
+  const int32_t qa = max(a, (int32_t)(block_p0 + w4 * (kWgWindow / 4)));
+  const int32_t qb = min(b, (int32_t)(block_p0 + (w4 + 1) * (kWgWindow / 4)));
   float* mine = coop_sum + (size_t)w4 * d;
   if (qa < qb) {
     row_sum_kahan<DT>(tokens, perm, qa, qb, k, cpr, row_bytes, [&](uint32_t c, const float (&acc)[E]) {
@@ -189,6 +192,10 @@ __device__ __forceinline__ void long_cluster_wg_window(
   } else {
     for (uint32_t i = lane; i < d; i += 64) mine[i] = 0.0f;
   }
+  const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[s]);
+  const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[s + 1]);
+  const uint32_t m0 = (uint32_t)lo / kWgWindow, m1 = (uint32_t)(hi - 1) / kWgWindow;
+  const uint32_t first_slot = 2 * m0 + ((uint32_t)lo % kWgWindow != 0 ? 1u : 0u);
   __syncthreads();
   if (w4 == 0) {
     float* out_row = partial + (size_t)slot * d;
@@ -201,56 +208,62 @@ __device__ __forceinline__ void long_cluster_wg_window(
       }
       *(float4*)(out_row + i) = v;
     }
-    const int32_t lo = __builtin_amdgcn_readfirstlane(seg_offsets[s]);
-    const int32_t hi = __builtin_amdgcn_readfirstlane(seg_offsets[s + 1]);
-    const uint32_t m0 = (uint32_t)lo / kWgWindow, m1 = (uint32_t)(hi - 1) / kWgWindow;
-    const uint32_t first_slot = 2 * m0 + ((uint32_t)lo % kWgWindow != 0 ? 1u : 0u);
     __threadfence();  // the partial row is visible device-wide before the counter moves
-    uint32_t old = 0;
-    if (lane == 0) old = atomicAdd(&counters[first_slot], 1u);
-    old = __builtin_amdgcn_readfirstlane(old);
-    if (old == m1 - m0) {
-      __threadfence();  // last block of the cluster: every other partial row is complete and visible
-      const uint32_t nwin = m1 - m0 + 1;
-      const float fn = (float)(hi - lo);
-      char* dst = centroids + (size_t)s * row_bytes;
-      constexpr int kRows = 4;
-      for (uint32_t c = lane; c < cpr; c += 64) {
-        float acc[E], comp[E];
+    if (lane == 0) *last_flag = atomicAdd(&counters[first_slot], 1u) == m1 - m0 ? 1u : 0u;
+  }
+  __syncthreads();    // the flag is set; the four LDS rows are free again
+  if (*last_flag == 0u) return;   // the same for all four waves
+  __threadfence();    // last block of the cluster: every other partial row is complete and visible
+  const uint32_t nwin = m1 - m0 + 1;
+  const uint32_t per = (nwin + 3) / 4;
+  const uint32_t j0 = min(w4 * per, nwin), j1 = min(j0 + per, nwin);
+  constexpr int kRows = 4;
+  for (uint32_t c = lane; c < cpr; c += 64) {
+    float acc[E], comp[E];
 #pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] = comp[i] = 0.0f;
-        for (uint32_t j = 0; j < nwin; j += kRows) {
-          float x[kRows][E];
+    for (int i = 0; i < E; ++i) acc[i] = comp[i] = 0.0f;
+    for (uint32_t j = j0; j < j1; j += kRows) {
+      float x[kRows][E];
 #pragma unroll
-          for (int u = 0; u < kRows; ++u) {
-            const uint32_t jj = min(j + u, nwin - 1);
-            const float* src = partial + (size_t)(jj == 0 ? first_slot : 2 * (m0 + jj)) * d + (size_t)c * E;
+      for (int u = 0; u < kRows; ++u) {
+        const uint32_t jj = min(j + u, j1 - 1);
+        const float* src = partial + (size_t)(jj == 0 ? first_slot : 2 * (m0 + jj)) * d + (size_t)c * E;
 #pragma unroll
-            for (int i = 0; i < E; i += 4) {
-              const float4 v = *(const float4*)(src + i);
-              x[u][i] = v.x; x[u][i + 1] = v.y; x[u][i + 2] = v.z; x[u][i + 3] = v.w;
-            }
-          }
+        for (int i = 0; i < E; i += 4) {
+          const float4 v = *(const float4*)(src + i);
+          x[u][i] = v.x; x[u][i + 1] = v.y; x[u][i + 2] = v.z; x[u][i + 3] = v.w;
+        }
+      }
 #pragma unroll
-          for (int u = 0; u < kRows; ++u) {
-            if (j + u < nwin) {
+      for (int u = 0; u < kRows; ++u) {
+        if (j + u < j1) {
 #pragma unroll
-              for (int i = 0; i < E; ++i) {
-                const float y = x[u][i] - comp[i];
-                const float t = acc[i] + y;
-                comp[i] = (t - acc[i]) - y;
-                acc[i] = t;
-              }
-            }
+          for (int i = 0; i < E; ++i) {
+            const float y = x[u][i] - comp[i];
+            const float t = acc[i] + y;
+            comp[i] = (t - acc[i]) - y;
+            acc[i] = t;
           }
         }
-        if (mean) {
-#pragma unroll
-          for (int i = 0; i < E; ++i) acc[i] /= fn;
-        }
-        store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
       }
     }
+#pragma unroll
+    for (int i = 0; i < E; i += 4)
+      *(float4*)(mine + (size_t)c * E + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+  }
+  __syncthreads();
+  const float fn = (float)(hi - lo);
+  char* dst = centroids + (size_t)s * row_bytes;
+  for (uint32_t c = threadIdx.x; c < cpr; c += 256) {
+    float acc[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      acc[i] = coop_sum[(size_t)c * E + i];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) acc[i] += coop_sum[((size_t)w * cpr + c) * E + i];
+      if (mean) acc[i] /= fn;
+    }
+    store16_stream(dst + c * 16, Piece<DT>::narrow(acc));
   }
   __syncthreads();  // before the LDS rows are used again
 }
@@ -463,7 +476,7 @@ void launch_lpr(const void* tokens, const int32_t* perm, const int32_t* seg_offs
   const uint32_t blocks = (uint32_t)((waves + 3) / 4);
   const size_t coop_bytes = (size_t)4 * cpr * Piece<DT>::kElems * sizeof(float);  // four partial rows in binary32
   const bool coop = LPR == 64 && coop_bytes <= kCoopMaxLds;
-  hipLaunchKernelGGL((centroid_kernel<DT, LPR>), grid_of_blocks(blocks), dim3(256), coop ? coop_bytes : 0, stream,
+  hipLaunchKernelGGL((centroid_kernel<DT, LPR>), grid_of_blocks(blocks), dim3(256), coop ? coop_bytes + 16 : 0, stream,
                      (const char*)tokens, perm, seg_offsets, seg_of, num_segments, (char*)centroids, partial, counters,
                      (uint32_t)N, (uint32_t)k, cpr, mean ? 1u : 0u, coop ? 1u : 0u);
 }
