@@ -167,7 +167,7 @@ __device__ __forceinline__ void long_cluster_window(
 // brings the counter to the cluster's block count adds the partial rows in position order, again a quarter per
 // wave joined through LDS in wave order, so the result does not depend on which workgroup came last.
 // Called by all four waves of the workgroup with the same arguments (barriers inside).
-constexpr uint32_t kWgWindow = 4 * kCentroidWindow;
+constexpr uint32_t kWgWindow = 2 * kCentroidWindow;   // measured: 128 and 512 positions per block are both slower
 static_assert(kWgWindow <= (uint32_t)kWindowMin, "a block meets at most two clusters that are cut into blocks");
 
 template <typename DT>
