@@ -250,6 +250,8 @@ def main():
                      "avg_launch_ms": float(dec_ms)},
         "stages_ms": {"hash": float(hash_ms), "compress": float(comp_ms), "decompress": float(dec_ms)},
         "stages_p50_ms": {n: float(np.median(stage_ms[:, j])) for j, n in enumerate(("hash", "compress", "decompress"))},
+        "stages_p10_ms": {n: float(np.percentile(stage_ms[:, j], 10)) for j, n in enumerate(("hash", "compress", "decompress"))},
+        "stages_p90_ms": {n: float(np.percentile(stage_ms[:, j], 90)) for j, n in enumerate(("hash", "compress", "decompress"))},
         "hash_mfma": {"tflops": hash_flops / (hash_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS[cfg.dtype],
                       "frac": hash_flops / (hash_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype],
                       "token_read_gbs": T * row / (hash_ms * 1e-3) / 1e9},
