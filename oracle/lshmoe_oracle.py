@@ -18,7 +18,9 @@ Pins (tests/test_oracle_*.py): pure-Python brute force on tiny inputs, the
 cross-polytope invariants (positive scaling, negation, row permutation of R),
 identity / orthonormal closed forms, dict- and numpy.unique-based grouping,
 mass conservation, exact reconstruction for singleton buckets, the linear
-expert closed form; for the backward pass central finite differences of the
+expert closed form, hand-worked gate-weighted combines (shared two-member
+clusters, unequal weights) and the weighted-sum identity over the unweighted
+rows, a hand-worked case of the row-scaled error metric; for the backward pass central finite differences of the
 forward functions of this file, its closed forms for one-member clusters and
 for an identity expert, and gradient mass conservation.  Absolute values of
 the whole path on the synthetic workloads have no printed counterpart in the

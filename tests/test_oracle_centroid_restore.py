@@ -161,3 +161,67 @@ def test_gate_weighted_combine_by_hand():
     w = np.array([[0.25, 0.75]], np.float32)
     y = restore_ref(x, c, ec, g["seg_of"], 2, "f32", gate_weight=w)
     assert y.tolist() == [[10.0, 14.0]]
+
+
+def test_gate_weighted_combine_two_tokens_shared_cluster_by_hand():
+    # Two tokens, both routed to experts (0, 1), both in bucket 0: clusters {a0, a2} (expert 0) and {a1, a3}
+    # (expert 1), each with centroid c = (x0 + x1)/2 = (2, 5) and non-zero residuals -+(1, 2).
+    #   Y[a0] = EC0 + (x0 - c) = (10, 20) + (-1, 2) = ( 9, 22)     Y[a1] = EC1 + (x0 - c) = (100, 200) + (-1, 2) = ( 99, 202)
+    #   Y[a2] = EC0 + (x1 - c) = (11, 18)                          Y[a3] = EC1 + (x1 - c) = (101, 198)
+    #   out[0] = 0.25*Y[a0] + 0.5*Y[a1] = (2.25 + 49.5, 5.5 + 101) = (51.75, 106.5)     (weights need not sum to 1)
+    #   out[1] = 2*Y[a2] - 1*Y[a3]      = (22 - 101, 36 - 198)     = (-79, -162)
+    x = np.array([[1.0, 7.0], [3.0, 3.0]], np.float32)
+    expert = np.array([[0, 1], [0, 1]], np.int32)
+    g = group_ref(expert, np.zeros(2, np.uint64), 2)
+    assert g["seg_of"].tolist() == [0, 1, 0, 1]
+    c = centroid_ref(x, g["perm"], g["seg_offsets"], 2, "f32")
+    assert c.tolist() == [[2.0, 5.0], [2.0, 5.0]]
+    ec = np.array([[10.0, 20.0], [100.0, 200.0]], np.float32)
+    w = np.array([[0.25, 0.5], [2.0, -1.0]], np.float32)
+    out = restore_ref(x, c, ec, g["seg_of"], 2, "f32", gate_weight=w)
+    assert out.shape == (2, 2)
+    assert out.tolist() == [[51.75, 106.5], [-79.0, -162.0]]
+    # without the residual only the expert outputs are mixed
+    out0 = restore_ref(x, c, ec, g["seg_of"], 2, "f32", no_residual=True, gate_weight=w)
+    assert out0.tolist() == [[52.5, 105.0], [-80.0, -160.0]]
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_gate_weighted_combine_is_the_weighted_sum_of_the_unweighted_rows(k):
+    # Eq. 2 over Eq. 4/5: restore_ref(gate_weight=w)[t] == sum_j w[t, j] * restore_ref(...)[t*k + j], nothing rounded
+    x, expert, bucket, g = _case(21 + k, T=300, d=10, k=k, E=5, nb=12, dtype="f32")
+    rng = np.random.default_rng(99)
+    x64 = widen(x, "f32")
+    _, c64 = centroid_ref(x, g["perm"], g["seg_offsets"], k, "f32", return_f64=True)
+    assert (np.diff(g["seg_offsets"]) > 1).sum() > 20            # residuals are not all zero
+    ec64 = rng.standard_normal((g["S"], x.shape[1]))
+    w = rng.standard_normal((x.shape[0], k))
+    y = restore_ref(x64, c64, ec64, g["seg_of"], k, "f64")        # [N, d]
+    assert np.abs(y - ec64[g["seg_of"]]).max() > 0.1
+    out = restore_ref(x64, c64, ec64, g["seg_of"], k, "f64", gate_weight=w)
+    ref = np.zeros((x.shape[0], x.shape[1]))
+    for t in range(x.shape[0]):
+        for j in range(k):
+            ref[t] += w[t, j] * y[t * k + j]
+    assert out.shape == ref.shape
+    assert np.allclose(out, ref, rtol=1e-13, atol=1e-13)
+
+
+# ------------------------------------------------------------------ tolerance metric
+def test_row_rel_err_by_hand():
+    # row 0: |got - ref| max = 0.5 (at ref 100), row maximum of |ref| = 100       -> 0.005
+    # row 1: |got - ref| max = 0.002 (at ref 0.01), row maximum of |ref| = 0.02   -> 0.1
+    # row 2: reference all zero -> denominator 1                                   -> 0.25
+    # A per-array maximum would give (0.005, 2e-5, 0.0025); |got| in the denominator (100.5, 0.021, 0.25) would
+    # give (0.004975.., 0.0952.., 1.0); a mean instead of a maximum, or an element-wise ratio, differs as well.
+    from oracle import row_rel_err
+    ref = np.array([[100.0, -1.0, 0.0], [0.01, -0.02, 0.0], [0.0, 0.0, 0.0]])
+    got = np.array([[100.5, -1.25, 0.0], [0.012, -0.021, 0.001], [0.0, -0.25, 0.125]])
+    err = row_rel_err(got, ref)
+    assert err.shape == (3,)
+    assert np.allclose(err, [0.005, 0.1, 0.25], rtol=1e-12, atol=0)
+    # symmetric in the sign of the error, zero for equal arrays, and rows do not influence one another
+    assert np.allclose(row_rel_err(2 * ref - got, ref), err, rtol=1e-9)
+    assert np.array_equal(row_rel_err(ref, ref), np.zeros(3))
+    assert np.allclose(row_rel_err(got[1:2], ref[1:2]), [0.1], rtol=1e-12)
+    assert row_rel_err(np.zeros((0, 3)), np.zeros((0, 3))).shape == (0,)
