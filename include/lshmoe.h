@@ -32,6 +32,10 @@
  *     of binary32).  All sums are accumulated in binary32 and rounded to the
  *     storage type once, round-to-nearest-even.
  *   - The row size d * sizeof(element) must be a multiple of 16 bytes.
+ *   - Entry points that move [N, d] rows (compress, decompress, the backward
+ *     pair) address 16-byte pieces with 32-bit indices inside one launch:
+ *     N * d * sizeof(element) / 16 must not exceed 2^32 - 256, i.e. about 64 GiB
+ *     of rows per call (LSHMOE_ERR_UNSUPPORTED beyond).
  *   - Return value: LSHMOE_OK or an error code; nothing is enqueued on a host
  *     side error.  lshmoe_last_error() gives a thread-local description.
  *     Arguments are checked on the host before any GPU call, so the checks
@@ -104,9 +108,12 @@ lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E,
  *   bucket [T]      out  uint64
  *
  * The products are exact in binary32 for bf16 inputs and are accumulated in
- * binary32, so a token whose two largest |y_i| differ by less than about 1e-5
- * relative may land on the other of the two vertices than exact arithmetic
- * gives.
+ * binary32 (16 products per matrix instruction), so every y_i carries an error
+ * of at most (d/16 + 8) * 2^-24 * sum_j |R_l[i][j] x_j|: about 3e-5 of the
+ * largest |y_i| for Gaussian data at d = 1024, typically a tenth of that.  A
+ * token whose two largest |y_i| differ by less than 1e-4 relative may therefore
+ * land on the other of the two vertices than exact arithmetic gives; apart from
+ * such near ties the codes are those of exact arithmetic.
  * Errors: NULL pointer; T, d, L, r <= 0; r < 2 or (2r)^L >= 2^63
  * (UNSUPPORTED); r > 256 (UNSUPPORTED); d*sizeof(element) not a multiple of 16
  * (UNSUPPORTED); launch failure (HIP).

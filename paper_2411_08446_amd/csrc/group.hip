@@ -921,7 +921,7 @@ hipError_t launch_scatter(const KeySource& src, uint32_t N, const PassArgs& a, u
     raised.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(kern, dim3(a.nblk), dim3(kSortThreads), kScatterLds, stream, src, N, a, dkey, didx);
-  return hipSuccess;
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -996,6 +996,13 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
   return true;
 }
 
+// A launch followed by a look at its status: a refused launch ends the call before anything else is enqueued.
+#define LSHMOE_LAUNCH(...)                                                        \
+  do {                                                                            \
+    hipLaunchKernelGGL(__VA_ARGS__);                                              \
+    if (hipError_t launch_err = hipGetLastError(); launch_err != hipSuccess) return launch_err; \
+  } while (0)
+
 hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint64_t* bucket, int k, int E,
                         int32_t* seg_offsets, int32_t* seg_expert, int32_t* expert_offsets, int32_t* perm,
                         int32_t* seg_of, int32_t* num_segments, char* ws, hipStream_t stream) {
@@ -1023,7 +1030,7 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     a.seg_offsets = seg_offsets; a.seg_expert = seg_expert; a.expert_offsets = expert_offsets;
     a.perm = perm; a.seg_of = seg_of; a.num_segments = num_segments;
     a.window_counters = (uint32_t*)(ws + plan.off_counters);
-    hipLaunchKernelGGL(small_group_kernel, dim3(1), dim3(kSmallWaves * 64), 0, stream, src, a);
+    LSHMOE_LAUNCH(small_group_kernel, dim3(1), dim3(kSmallWaves * 64), 0, stream, src, a);
     return hipGetLastError();
   }
   const uint64_t* sorted_key = nullptr;
@@ -1039,8 +1046,8 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     // the histogram kernel also clears the per-tile head counts that the bin kernels add to
     hipError_t e = hipSuccess;
 #define LSHMOE_GLOBAL_PASS(TILE)                                                                                     \
-    hipLaunchKernelGGL((sort_hist_kernel<true, true, TILE>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table, \
-                       blocksum, plan.seg_blocks + 1);                                                                  \
+    LSHMOE_LAUNCH((sort_hist_kernel<true, true, TILE>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table, \
+                  blocksum, plan.seg_blocks + 1);                                                                       \
     e = launch_scatter<true, true, TILE>(src, N, a, keybuf[0], idxbuf[0], stream)
     if (plan.tile == 512) { LSHMOE_GLOBAL_PASS(512); }
     else if (plan.tile == 1024) { LSHMOE_GLOBAL_PASS(1024); }
@@ -1064,10 +1071,10 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     b.tile_heads = blocksum;
     b.chunk_heads = (uint4*)(ws + plan.off_chunkheads);
     const dim3 chunks((uint32_t)kGroupBins + (N + kBinChunk - 1) / kBinChunk), threads(kBinThreads);
-    hipLaunchKernelGGL(bin_sort_kernel, chunks, threads, kBinSortLds, stream, b);
-    hipLaunchKernelGGL(bin_merge_kernel, dim3(chunks.x * kMergeSlices), threads, 0, stream, b);
+    LSHMOE_LAUNCH(bin_sort_kernel, chunks, threads, kBinSortLds, stream, b);
+    LSHMOE_LAUNCH(bin_merge_kernel, dim3(chunks.x * kMergeSlices), threads, 0, stream, b);
     // the heads per numbering tile are known: number the clusters (the tile count is within kSelfPrefixMaxTiles here)
-    hipLaunchKernelGGL(seg_write_kernel<true>, dim3(plan.seg_blocks), dim3(kSegThreads), 0, stream,
+    LSHMOE_LAUNCH(seg_write_kernel<true>, dim3(plan.seg_blocks), dim3(kSegThreads), 0, stream,
                        (const uint64_t*)keybuf[1], perm, N, (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert,
                        expert_offsets, seg_of, num_segments, (uint32_t*)(ws + plan.off_counters),
                        (const uint4*)b.chunk_heads, (const uint32_t*)(bin_start + kGroupBins + 1));
@@ -1085,18 +1092,18 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     hipError_t e = hipSuccess;
     if (plan.fused) {
       if (p == 0) {
-        hipLaunchKernelGGL((sort_hist_kernel<true, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+        LSHMOE_LAUNCH((sort_hist_kernel<true, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
         e = launch_scatter<true, true>(src, N, a, dkey, didx, stream);
       } else {
-        hipLaunchKernelGGL((sort_hist_kernel<false, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+        LSHMOE_LAUNCH((sort_hist_kernel<false, true>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
         e = launch_scatter<false, true>(src, N, a, dkey, didx, stream);
       }
     } else {
       if (p == 0)
-        hipLaunchKernelGGL((sort_hist_kernel<true, false>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+        LSHMOE_LAUNCH((sort_hist_kernel<true, false>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
       else
-        hipLaunchKernelGGL((sort_hist_kernel<false, false>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
-      hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, table, (a.mask + 1u) * nblk);
+        LSHMOE_LAUNCH((sort_hist_kernel<false, false>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table);
+      LSHMOE_LAUNCH(scan_kernel, dim3(1), dim3(1024), 0, stream, table, (a.mask + 1u) * nblk);
       e = p == 0 ? launch_scatter<true, false>(src, N, a, dkey, didx, stream)
                  : launch_scatter<false, false>(src, N, a, dkey, didx, stream);
     }
@@ -1106,19 +1113,21 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     sorted_key = dkey;
   }
   const uint32_t sblk = plan.seg_blocks;
-  hipLaunchKernelGGL(seg_count_kernel, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, N, sblk, blocksum,
+  LSHMOE_LAUNCH(seg_count_kernel, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, N, sblk, blocksum,
                      (uint32_t*)(ws + plan.off_counters));
   if (sblk <= (uint32_t)kSelfPrefixMaxTiles) {
-    hipLaunchKernelGGL(seg_write_kernel<true>, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, perm, N,
+    LSHMOE_LAUNCH(seg_write_kernel<true>, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, perm, N,
                        (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert, expert_offsets, seg_of,
                        num_segments);
   } else {
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, blocksum, sblk + 1);
-    hipLaunchKernelGGL(seg_write_kernel<false>, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, perm, N,
+    LSHMOE_LAUNCH(scan_kernel, dim3(1), dim3(1024), 0, stream, blocksum, sblk + 1);
+    LSHMOE_LAUNCH(seg_write_kernel<false>, dim3(sblk), dim3(kSegThreads), 0, stream, sorted_key, perm, N,
                        (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert, expert_offsets, seg_of,
                        num_segments);
   }
   return hipGetLastError();
 }
+
+#undef LSHMOE_LAUNCH
 
 }  // namespace lshmoe

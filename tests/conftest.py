@@ -27,3 +27,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter, exitstatus, config):
+    """Worst row-scaled error per stage seen by the GPU parity harness in this session (empty without a GPU)."""
+    harness = sys.modules.get("gpu_harness")
+    if harness is None or not getattr(harness, "WORST", None):
+        return
+    terminalreporter.write_line("worst row-scaled error against the oracle, per stage (asserted tolerance):")
+    for (what, dtype), err in sorted(harness.WORST.items()):
+        terminalreporter.write_line("  %-40s %-5s %.3e  (%.3e)" % (what, dtype, err, harness.TOL[dtype]))
+    terminalreporter.write_line("largest top-2 margin at which a hash digit took the runner-up vertex: %.3e (accepted below %.0e)"
+                                % (harness.WORST_FLIP_MARGIN[0], harness.TIE_MARGIN))

@@ -18,7 +18,17 @@ import oracle
 import paper_2411_08446_amd as lsh
 
 TIE_MARGIN = 1e-4
-TOL = {"f32": 1e-5, "bf16": 2e-2}     # row-scaled: max_j |gpu - ref| <= tol * max_j |ref|
+# Row-scaled tolerances: max_j |gpu - ref| <= tol * max_j |ref| per output row.  The bar stated for this path is
+# 1e-5 (binary32) and 2e-2 (bf16).  The bf16 figure asserted here is tighter and is what the arithmetic gives: both
+# sides hold the result in binary32 or better and round once to bf16, so they can differ by one bf16 unit in the
+# last place at most, and for an element no larger than the row maximum that unit is at most 2^-7 of the maximum.
+TOL = {"f32": 1e-5, "bf16": 2.0 ** -7}
+STATED_TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+# worst row error seen per (stage, dtype) in this process; the test session prints it at the end
+WORST: dict = {}
+# largest relative top-2 margin at which a hash digit differed from the oracle's (accepted runner-up flips)
+WORST_FLIP_MARGIN = [0.0]
 
 
 def to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
@@ -59,6 +69,8 @@ def check_hash(bucket_gpu: np.ndarray, tokens, rot, dtype):
     diff = digits != code
     bad = diff & ~((margin < TIE_MARGIN) & (digits == runner))
     assert not bad.any(), "hash mismatch away from a near tie at (token, hash) %s" % (np.argwhere(bad)[:8].tolist(),)
+    if diff.any():
+        WORST_FLIP_MARGIN[0] = max(WORST_FLIP_MARGIN[0], float(margin[diff].max()))
     return int(diff.sum()), int((margin < TIE_MARGIN).sum())
 
 
@@ -67,7 +79,10 @@ def assert_rows_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str, t
     err = oracle.row_rel_err(oracle.widen(got, dtype), oracle.widen(ref, dtype))
     worst = int(np.argmax(err)) if err.size else -1
     assert err.size == 0 or err[worst] <= tol, "%s: row %d off by %.3g (tol %.3g)" % (what, worst, err[worst], tol)
-    return float(err.max()) if err.size else 0.0
+    top = float(err.max()) if err.size else 0.0
+    stage = what.rstrip("0123456789 ")               # callers may append a row or sample number
+    WORST[(stage, dtype)] = max(WORST.get((stage, dtype), 0.0), top)
+    return top
 
 
 def run_and_check(tokens: np.ndarray, rot: np.ndarray, expert: np.ndarray, E: int, dtype: str, expert_fn,
@@ -100,6 +115,7 @@ def run_and_check(tokens: np.ndarray, rot: np.ndarray, expert: np.ndarray, E: in
     # poison the outputs so stale values cannot pass
     for t in (out.seg_offsets, out.seg_expert, out.expert_offsets, out.perm, out.seg_of, out.num_segments):
         t.fill_(-7)
+    out.workspace.fill_(0xA5)                         # the call must not rely on what the workspace holds
     lsh.lshmoe_compress(xt, et, bt, E, L, r, out)
     torch.cuda.synchronize()
     g = oracle.group_ref(expert, bucket, E)

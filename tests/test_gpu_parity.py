@@ -413,9 +413,12 @@ def test_hash_gate(H, dtype, T, L, r, E):
     bound = (d / 16 + 8) * 2.0 ** -24 * (xa @ wa.T)
     worst = np.max(np.abs(got - ref) - bound)
     assert worst <= 0.0, "gate logits off by %.3g beyond the accumulation bound" % worst
-    if E >= 16:
+    print("gate logits T=%d L=%d r=%d E=%d %s: largest |error| / bound = %.3f" %
+          (T, L, r, E, dtype, float(np.max(np.abs(got - ref) / np.maximum(bound, 1e-300)))), flush=True)
+    if E >= 4:
         err = oracle.row_rel_err(got, ref)
         assert err.max() <= 1e-5, "gate logits: row %d off by %.3g" % (int(err.argmax()), err.max())
+        H.WORST[("gate logits", "f32")] = max(H.WORST.get(("gate logits", "f32"), 0.0), float(err.max()))
 
 
 def test_path_replays_from_a_graph(H):
