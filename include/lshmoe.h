@@ -12,6 +12,7 @@
  *   lshmoe_hash_gate            lshmoe_hash that also returns the gate's projection of the tokens (Eq. 1)
  *   lshmoe_decompress_combine   lshmoe_decompress fused with the gate-weighted sum over a token's experts (Eq. 2)
  *   lshmoe_decompress_backward, lshmoe_compress_backward   gradients through the two calls above
+ *   lshmoe_compress_static      lshmoe_compress on scratch memory built into the library (allocates nothing)
  *
  * Notation: T tokens of dimension d; every token is routed to k distinct
  * experts out of E (assignment a = t*k + j is token t's j-th expert, N = T*k
@@ -179,6 +180,28 @@ lshmoe_status lshmoe_compress(const void* tokens, const int32_t* expert, const u
                               int32_t* expert_offsets, int32_t* perm, int32_t* seg_of,
                               int32_t* num_segments,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * lshmoe_compress for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace pair), same
+ * kernels and bit-identical outputs; the scratch is an array of LSHMOE_STATIC_SCRATCH_BYTES bytes that is part of
+ * the library's device image (every GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing; its first call on a device looks up that device's address of the array.
+ *
+ * Sizes whose lshmoe_workspace_bytes exceeds LSHMOE_STATIC_SCRATCH_BYTES are refused with LSHMOE_ERR_WORKSPACE and
+ * nothing is enqueued (the five paper-shaped layers of up to T = 65536, d = 1024, k = 2 fit).  All calls on one GPU
+ * share the one array: two calls that overlap on that GPU (different streams, or a graph replay beside an eager
+ * call) race; calls on one stream are ordered and safe.  What the array holds between calls is unspecified; the
+ * kernels clear what they need.
+ * Other errors: as for lshmoe_compress; failure to find the array's address (HIP).
+ */
+#define LSHMOE_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+lshmoe_status lshmoe_compress_static(const void* tokens, const int32_t* expert, const uint64_t* bucket,
+                                     int64_t T, int32_t d, int32_t k, int32_t E,
+                                     int32_t L, int32_t r, lshmoe_dtype dtype,
+                                     void* centroids, int32_t* seg_offsets, int32_t* seg_expert,
+                                     int32_t* expert_offsets, int32_t* perm, int32_t* seg_of,
+                                     int32_t* num_segments, void* stream);
 
 /*
  * Restore with residual compensation (Eq. 4 and Eq. 5; last loop of

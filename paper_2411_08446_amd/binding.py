@@ -63,6 +63,9 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.lshmoe_compress.restype = ctypes.c_int
     lib.lshmoe_compress.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_int,
                                     vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.lshmoe_compress_static.restype = ctypes.c_int
+    lib.lshmoe_compress_static.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_int,
+                                           vp, vp, vp, vp, vp, vp, vp, vp]
     lib.lshmoe_decompress.restype = ctypes.c_int
     lib.lshmoe_decompress.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
     lib.lshmoe_decompress_combine.restype = ctypes.c_int
@@ -186,6 +189,25 @@ def lshmoe_compress(tokens: torch.Tensor, expert: torch.Tensor, bucket: torch.Te
         _ptr(tokens), _ptr(expert, i32), _ptr(bucket, torch.int64), T, d, k, E, L, r, _dtype_code(tokens),
         _ptr(out.centroids), _ptr(out.seg_offsets, i32), _ptr(out.seg_expert, i32), _ptr(out.expert_offsets, i32),
         _ptr(out.perm, i32), _ptr(out.seg_of, i32), _ptr(out.num_segments, i32), ws_ptr, ws_bytes, _stream(stream)))
+
+
+def lshmoe_compress_static(tokens: torch.Tensor, expert: torch.Tensor, bucket: torch.Tensor, E: int, L: int, r: int,
+                           out: CompressOutputs, stream=None) -> None:
+    """lshmoe_compress on the library's built-in scratch: out.workspace is not used and nothing is allocated."""
+    T, d = tokens.shape
+    k = expert.shape[1]
+    if expert.shape[0] != T or bucket.numel() != T:
+        raise ValueError("expert must be [T, k] and bucket [T]")
+    N = T * k
+    if (out.centroids.shape != (N, d) or out.centroids.dtype != tokens.dtype or out.seg_offsets.numel() != N + 1
+            or out.seg_expert.numel() != N or out.expert_offsets.numel() != E + 1 or out.perm.numel() != N
+            or out.seg_of.numel() != N or out.num_segments.numel() != 1):
+        raise ValueError("output buffers do not match T, k, d, E")
+    i32 = torch.int32
+    _check(load_library().lshmoe_compress_static(
+        _ptr(tokens), _ptr(expert, i32), _ptr(bucket, torch.int64), T, d, k, E, L, r, _dtype_code(tokens),
+        _ptr(out.centroids), _ptr(out.seg_offsets, i32), _ptr(out.seg_expert, i32), _ptr(out.expert_offsets, i32),
+        _ptr(out.perm, i32), _ptr(out.seg_of, i32), _ptr(out.num_segments, i32), _stream(stream)))
 
 
 def lshmoe_decompress(tokens: torch.Tensor, centroids: torch.Tensor, expert_out: torch.Tensor, seg_of: torch.Tensor,

@@ -4,6 +4,8 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <atomic>
+
 #include "../../include/lshmoe.h"
 #include "kernels.h"
 
@@ -82,6 +84,30 @@ lshmoe_status check_rows_shape(int64_t T, int d, int k, int dt) {
     return fail(LSHMOE_ERR_UNSUPPORTED, "N = T*k = %lld assignments; the limit is 2^30 - 1", (long long)(T * (int64_t)k));
   if ((uint64_t)T * (uint64_t)k * ((size_t)d * item_size(dt) / 16) > 0xffffff00ull)
     return fail(LSHMOE_ERR_UNSUPPORTED, "N*d is too large for one launch");
+  return LSHMOE_OK;
+}
+
+// Scratch of lshmoe_compress_static: device memory that belongs to the library image, so that the call needs no
+// allocation.  Every GPU the library runs on holds its own copy until the process ends.  In host code the name is
+// only a handle; the device address is looked up once per device and kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = LSHMOE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+lshmoe_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail("hipGetDevice", e);
+  if (dev < 0 || dev >= kMaxDevices) return fail(LSHMOE_ERR_UNSUPPORTED, "device ordinal %d; the limit is %d", dev, kMaxDevices - 1);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail("hipGetSymbolAddress(scratch)", e);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // two threads racing here store the same address
+  }
+  *out = p;
   return LSHMOE_OK;
 }
 
@@ -171,6 +197,25 @@ lshmoe_status lshmoe_compress(const void* tokens, const int32_t* expert, const u
                               /*mean=*/true, s);
   if (e != hipSuccess) return hip_fail("centroid launch", e);
   return ok();
+}
+
+lshmoe_status lshmoe_compress_static(const void* tokens, const int32_t* expert, const uint64_t* bucket, int64_t T,
+                                     int32_t d, int32_t k, int32_t E, int32_t L, int32_t r, lshmoe_dtype dtype,
+                                     void* centroids, int32_t* seg_offsets, int32_t* seg_expert, int32_t* expert_offsets,
+                                     int32_t* perm, int32_t* seg_of, int32_t* num_segments, void* stream) {
+  if (!tokens || !expert || !bucket || !centroids || !seg_offsets || !seg_expert || !expert_offsets || !perm ||
+      !seg_of || !num_segments)
+    return fail(LSHMOE_ERR_NULL, "an input or output pointer is NULL");
+  lshmoe::GroupPlan plan;
+  if (lshmoe_status st = check_compress_shape(T, d, k, E, L, r, (int)dtype, &plan)) return st;
+  if (plan.total_bytes > kStaticScratchBytes)
+    return fail(LSHMOE_ERR_WORKSPACE,
+                "these sizes need %zu bytes of scratch; the built-in scratch of lshmoe_compress_static holds %zu "
+                "(use lshmoe_compress with a workspace of the caller's)", plan.total_bytes, kStaticScratchBytes);
+  void* ws = nullptr;
+  if (lshmoe_status st = static_scratch(&ws)) return st;
+  return lshmoe_compress(tokens, expert, bucket, T, d, k, E, L, r, dtype, centroids, seg_offsets, seg_expert,
+                         expert_offsets, perm, seg_of, num_segments, ws, kStaticScratchBytes, stream);
 }
 
 lshmoe_status lshmoe_decompress(const void* tokens, const void* centroids, const void* expert_out,
