@@ -39,13 +39,25 @@ def _fail(msg: str, code: int = 2):
 
 
 def cpu_baseline(w, sample_tokens: int):
-    """Time the CPU oracle, as it stands, on the first `sample_tokens` tokens."""
-    import numpy as np
+    """Time the CPU oracle, as it stands, on the arrays of the benched workload (all of them when sample_tokens is 0,
+    else the first sample_tokens tokens).  The oracle is numpy: its rotation step is a BLAS matmul and is timed
+    twice, on one thread and on every core the process may use; its other steps are single-threaded numpy and
+    are timed once."""
     import oracle
-    from workloads import synth
     cfg = w.cfg
-    Ts = min(sample_tokens, cfg.T)
+    Ts = cfg.T if sample_tokens <= 0 else min(sample_tokens, cfg.T)
     tokens, expert = w.tokens[:Ts], w.expert[:Ts]
+    try:
+        import threadpoolctl
+        threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+    except Exception:
+        threadpoolctl, threads = None, 1
+    hash_1 = None
+    if threadpoolctl is not None and threads > 1:
+        with threadpoolctl.threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            oracle.hash_ref(tokens, w.rot, cfg.dtype)
+            hash_1 = time.perf_counter() - t0
     t0 = time.perf_counter()
     bucket, _, _, _ = oracle.hash_ref(tokens, w.rot, cfg.dtype)
     t1 = time.perf_counter()
@@ -53,25 +65,29 @@ def cpu_baseline(w, sample_tokens: int):
     t2 = time.perf_counter()
     c = oracle.centroid_ref(tokens, g["perm"], g["seg_offsets"], cfg.k, cfg.dtype)
     t3 = time.perf_counter()
-    # expert output stand-in for the sample: any [S, d] array serves for timing the restore
+    # expert output stand-in: any [S, d] array serves for timing the restore
     y = oracle.restore_ref(tokens, c, c, g["seg_of"], cfg.k, cfg.dtype)
     t4 = time.perf_counter()
     del y
-    try:
-        import threadpoolctl
-        threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
-    except Exception:
-        threads = 1
+    rest = t4 - t1
     total = t4 - t0
+    total_1 = (hash_1 if hash_1 is not None else t1 - t0) + rest
+    what = "all %d tokens" % cfg.T if Ts == cfg.T else "first %d of %d tokens" % (Ts, cfg.T)
     return {
         "value": Ts / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-        "sample": "first %d of %d tokens of the same workload; numpy float64 oracle, matmul step on %d BLAS "
-                  "threads, other steps on 1" % (Ts, cfg.T, threads),
-        "seconds": {"hash": t1 - t0, "group": t2 - t1, "centroid": t3 - t2, "restore": t4 - t3},
+        "sample": "%s of the benched workload (the same arrays); numpy float64 oracle; rotation matmul on %d BLAS "
+                  "threads, grouping / centroid / restore steps single-threaded numpy" % (what, threads),
+        "value_single_thread": Ts / total_1,
+        "seconds": {"hash": t1 - t0, "hash_single_thread": hash_1 if hash_1 is not None else t1 - t0,
+                    "group": t2 - t1, "centroid": t3 - t2, "restore": t4 - t3},
     }
 
 
-EVENT_EVERY = 8   # steps between two steps whose stages are timed with events
+def event_stride(steps: int) -> int:
+    """Steps between two steps whose stages are timed with events: an event record costs about 3 us of stream time
+    (4 records: 13 us on a 250 us step), so long runs sample every 8th step; short runs sample more densely so that
+    any run of 10 steps or more still yields 8 or more intervals per stage."""
+    return max(1, min(8, steps // 10))
 
 
 def measured_peaks():
@@ -130,11 +146,12 @@ def main():
                     help="comma-separated numbers of hash functions, e.g. 2,4,6,8,10: adds supplementary_hash_count_sweep "
                          "(compression rate and step time per count, content gate, sigma 0.02)")
     ap.add_argument("--sweep-r", type=int, default=16, help="rotated dimensions per hash function in --sweep-hashes")
-    ap.add_argument("--peaks", action="store_true",
-                    help="also measure what this GPU sustains (streaming read, streaming copy, bf16 MFMA loop) and "
-                         "add measured_peaks to the line")
+    ap.add_argument("--no-peaks", dest="peaks", action="store_false",
+                    help="skip measuring what this GPU sustains (streaming read, streaming copy, bf16 MFMA loop: "
+                         "measured_peaks and the fractions against them)")
     ap.add_argument("--copies", type=int, default=2, help="independent input copies rotated between steps")
-    ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=0,
+                    help="tokens in the CPU-oracle baseline (0 = all tokens of the workload, the default; -1 = skip)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the loop, run one plain device-to-device copy of this many MiB (a kernel of known "
                          "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -210,8 +227,9 @@ def main():
 
     K = args.steps
     # Per-stage durations come from events on the launch stream inside the timed region.  An event record costs
-    # about 3 us of stream time, so only every EVENT_EVERY-th step carries them (4 records: 13 us on a 250 us step).
-    sampled = [i for i in range(K) if i % EVENT_EVERY == 0]
+    # about 3 us of stream time, so only every stride-th step carries them (see event_stride).
+    stride = event_stride(K)
+    sampled = [i for i in range(K) if i % stride == 0]
     events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(4)] for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -221,7 +239,7 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
     stage_ms = np.array([[events[i][j].elapsed_time(events[i][j + 1]) for j in range(3)] for i in sampled])
-    hash_ms, comp_ms, dec_ms = stage_ms.mean(axis=0)
+    hash_ms, comp_ms, dec_ms = np.median(stage_ms, axis=0)      # medians: a sample that caught a stall does not move them
 
     # algorithmic bytes of the restore kernel for this workload: expert-output row read and output row
     # written for every assignment; token row and centroid row read only by members of multi-member clusters
@@ -242,13 +260,20 @@ def main():
         "config": {"workload": "%s: T=%d d=%d k=%d E=%d L=%d r=%d, Gaussian mixture of %d centers, gate=%s" %
                                (cfg.name, T, d, k, E, L, r, cfg.centers, cfg.gate),
                    "tokens": T, "assignments": N, "segments": S, "compression_rate": S / N,
-                   "single_member_segments": n_single, "input_copies_rotated": copies, "stage_events_every": EVENT_EVERY},
+                   "single_member_segments": n_single, "input_copies_rotated": copies, "stage_events_every": stride, "stage_event_samples": len(sampled)},
         "roofline": {"kernel": "restore_kernel (lshmoe_decompress)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.gate)), "algorithmic_bytes": restore_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.gate)),
+                     "traffic_source": "profiles/path_t5_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
+                                       "earlier run of this kernel on this workload; not measured by this run)"
+                                       if MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.gate)) else None,
+                     "algorithmic_bytes": restore_bytes,
                      "algorithmic_bytes_without_singleton_skip": restore_bytes_noskip,
                      "avg_launch_ms": float(dec_ms)},
         "stages_ms": {"hash": float(hash_ms), "compress": float(comp_ms), "decompress": float(dec_ms)},
+        "stages_note": "medians of the sampled steps; compress = the grouping launches + the centroid kernel. The "
+                       "centroid kernel's token rows are partly still in the 256 MB last-level cache behind the hash, "
+                       "so its bytes per second can exceed what a streaming read from HBM sustains",
         "stages_p50_ms": {n: float(np.median(stage_ms[:, j])) for j, n in enumerate(("hash", "compress", "decompress"))},
         "stages_p10_ms": {n: float(np.percentile(stage_ms[:, j], 10)) for j, n in enumerate(("hash", "compress", "decompress"))},
         "stages_p90_ms": {n: float(np.percentile(stage_ms[:, j], 90)) for j, n in enumerate(("hash", "compress", "decompress"))},
@@ -282,12 +307,18 @@ def main():
         lsh.lshmoe_compress(px, pe, bucket, E, L, r, outs[0])
         torch.cuda.synchronize()
         pS = int(outs[0].num_segments.item())
+        plen = np.diff(outs[0].seg_offsets[:pS + 1].cpu().numpy())
+        p_single = int((plen == 1).sum())
 
-        def pstep():
+        def pstep(ev=None):
+            if ev: ev[0].record()
             lsh.lshmoe_hash(px, rot, bucket)
+            if ev: ev[1].record()
             lsh.lshmoe_compress(px, pe, bucket, E, L, r, outs[0])
+            if ev: ev[2].record()
             lsh.lshmoe_decompress(px, outs[0].centroids, ecs[0], outs[0].seg_of, outs[0].seg_offsets, k, ys[0],
                                   perm=outs[0].perm, num_segments=outs[0].num_segments)
+            if ev: ev[3].record()
         for _ in range(5):
             pstep()
         torch.cuda.synchronize()
@@ -296,9 +327,25 @@ def main():
             pstep()
         torch.cuda.synchronize()
         pms = (time.perf_counter() - tp0) * 1e3 / args.paper_regime_steps
+        # per-stage times of the same steps, with events on every step (outside the figure above)
+        pev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(min(args.paper_regime_steps, 30))]
+        for e4 in pev:
+            pstep(e4)
+        torch.cuda.synchronize()
+        pst = np.array([[e4[j].elapsed_time(e4[j + 1]) for j in range(3)] for e4 in pev])
+        p_hash, p_comp, p_dec = (float(v) for v in np.median(pst, axis=0))
+        p_restore_bytes = (pS + N + (N - p_single) + (pS - p_single)) * row + 4 * N + 4 * (pS + 1)
+        p_centroid_bytes = (N + pS) * row + 4 * N + 4 * (pS + 1)
         result["supplementary_paper_regime"] = {
-            "workload": "%s, gate=content, sigma=0.02" % cfg.name, "compression_rate": pS / N, "ms_per_step": pms,
-            "tokens_per_s": T / (pms * 1e-3), "steps": args.paper_regime_steps}
+            "workload": "%s, gate=content, sigma=0.02" % cfg.name, "compression_rate": pS / N, "segments": pS,
+            "single_member_segments": p_single, "largest_cluster": int(plen.max()),
+            "ms_per_step": pms, "tokens_per_s": T / (pms * 1e-3), "steps": args.paper_regime_steps,
+            "stages_ms": {"hash": p_hash, "compress": p_comp, "decompress": p_dec},
+            "restore": {"algorithmic_bytes": p_restore_bytes, "achieved_gbs": p_restore_bytes / (p_dec * 1e-3) / 1e9,
+                        "frac_of_hbm_peak": p_restore_bytes / (p_dec * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "centroid": {"algorithmic_bytes": p_centroid_bytes,
+                         "note": "the compress stage is the grouping launches plus the centroid kernel; the kernel "
+                                 "trace under profiles/ splits them"}}
         del px, pe
     # supplementary: the hash fused with the gate's projection of the tokens (logits [T, E])
     if d * item % 512 == 0 and r % 8 == 0 and E <= 128:
@@ -391,14 +438,14 @@ def main():
             "decompress_backward_ms": seg_ms, "decompress_backward_gbs": seg_bytes / (seg_ms * 1e-3) / 1e9,
             "compress_backward_ms": gtok_ms, "compress_backward_gbs": gtok_bytes / (gtok_ms * 1e-3) / 1e9}
     if args.peaks:
-        result["measured_peaks"] = measured_peaks()
-        result["roofline"]["frac_of_measured_copy_rate"] = (
-            MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.gate), restore_bytes) / (dec_ms * 1e-3) / 1e9
-            / result["measured_peaks"]["hbm_copy_gbs"])
-    if args.cpu_sample > 0:
-        result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample)
-    else:
-        result["cpu_baseline"] = None
+        mp = measured_peaks()
+        result["measured_peaks"] = mp
+        traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.gate))
+        result["roofline"]["frac_of_measured_read_rate"] = achieved / mp["hbm_read_gbs"]
+        result["roofline"]["frac_of_measured_copy_rate"] = (traffic if traffic else restore_bytes) / (dec_ms * 1e-3) / 1e9 / mp["hbm_copy_gbs"]
+        if cfg.dtype == "bf16":
+            result["hash_mfma"]["frac_of_measured_mfma_rate"] = result["hash_mfma"]["tflops"] / mp["mfma_bf16_tflops"]
+    result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample) if args.cpu_sample >= 0 else None
     print(json.dumps(result))
 
 
