@@ -30,6 +30,7 @@
 // mapping, so which k a lane supplies is free as long as A and B agree: the
 // lane half h = l/32 takes piece 2s + h of the chunk in step s.
 #include <atomic>
+#include <utility>
 
 #include "kernels.h"
 
@@ -61,6 +62,57 @@ constexpr int kPieces = 8;   // 16-byte pieces per row per chunk
 constexpr int kSteps = 4;    // MFMA steps per chunk (two pieces, one per lane half, per step)
 
 __device__ __forceinline__ int swizzle(int row, int piece) { return piece ^ (row & 7); }
+
+// Compile-time loop: f is called with std::integral_constant<int, 0> .. <int, N - 1>, so that every index derived
+// from it is a constant expression.
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// Arg-max of |y| over the rows a lane holds of one hash whose rows are the NT whole 32-row tiles T0 .. T0 + NT - 1 of
+// the lane's accumulators, for NTW token tiles at once (their chains are independent, which keeps the vector unit
+// busy).  One pass in ascending row order: a strictly larger magnitude replaces the candidate, so the lowest row
+// wins among equal magnitudes; the candidate starts as +0 at the lane's first row.  bv: value at the candidate;
+// bid: its row inside the hash, without the lane half's offset of 4 rows.
+template <int T0, int NT, int MTW, int NTW>
+__device__ __forceinline__ void scan_hash_tiles(const floatx16 (&acc)[MTW][NTW], float (&bv)[NTW], int (&bid)[NTW]) {
+  static_for<NTW>([&](auto uc) {
+    bv[decltype(uc)::value] = 0.0f;
+    bid[decltype(uc)::value] = 0;
+  });
+  static_for<NT * 16>([&](auto qc) {
+    constexpr int q = decltype(qc)::value;
+    constexpr int t = q / 16, j = q % 16;            // register j of tile T0 + t: row 32 t + 8 (j / 4) + 4 h + j % 4
+    static_for<NTW>([&](auto uc) {
+      constexpr int u = decltype(uc)::value;
+      const float v = acc[T0 + t][u][j];
+      if (fabsf(v) > fabsf(bv[u])) {
+        bv[u] = v;
+        bid[u] = 32 * t + 8 * (j / 4) + j % 4;
+      }
+    });
+  });
+}
+
+// Joins a lane's candidate with that of lane ^ 32, which holds the other 16 rows of every tile.  Returns the
+// magnitude pattern; row and sign of the winner are left in bi and neg.  -0 counts as positive.
+__device__ __forceinline__ uint32_t join_lane_halves(float bv, int& bi, bool& neg) {
+  uint32_t best = __float_as_uint(bv) & 0x7fffffffu;
+  neg = (__float_as_uint(bv) >> 31) != 0u && best != 0u;
+  const uint32_t obest = (uint32_t)__shfl_xor((int)best, 32, 64);
+  const int obi = __shfl_xor(bi, 32, 64);
+  const int oneg = __shfl_xor((int)neg, 32, 64);
+  if (obest > best || (obest == best && obi < bi)) {
+    best = obest;
+    bi = obi;
+    neg = oneg != 0;
+  }
+  return best;
+}
 
 template <typename DT, int MT, int NTK, int XDEPTH, int WAVES, int OCC, bool ALIGNED8, bool KTAIL>
 __global__ __launch_bounds__(WAVES * 64, OCC) void hash_kernel(const char* __restrict__ tokens, const char* __restrict__ rot,
@@ -335,13 +387,18 @@ template <int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX> struct Strea
 // GATE: E further rows (a gate projection W_g, same layout as R) are appended to the rows of the single hash
 // group; their products are written to logits[T][E] as binary32 instead of entering an arg-max, so that the
 // hash and the gate read the tokens once.  L = 0 computes the gate rows alone.
-template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX, bool GATE = false>
+// RC: 0, or the value of r when it is 32, 64, 128 or 256 and hash boundaries fall on tile boundaries of every
+// wave (the launcher checks): the arg-max then runs over compile-time row ranges, without a branch per block of
+// rows; it is a quarter to a third of the generic one's time, which at the largest shapes was a sixth of the kernel.
+template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX, bool GATE = false, int RC = 0>
 __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
     const char* __restrict__ tokens, const char* __restrict__ rot, uint64_t* __restrict__ bucket, uint32_t T,
     int row_pieces, int L, int r, int hpg, const char* __restrict__ gate_w = nullptr, int E = 0,
     float* __restrict__ logits = nullptr) {
   using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
   static_assert(!GATE || HALVES == 1, "the gate rows ride on the unsplit shapes");
+  static_assert(RC == 0 || (!GATE && (RC == 256 ? (MTW == 4 && HALVES == 2) : (RC % 32 == 0 && (MTW * 32) % RC == 0))),
+                "a compile-time r needs whole hashes per wave (or, for r = 256, half a hash)");
   constexpr int WAVES = S::kWaves, TH = WAVES * 64;
   constexpr int LR = S::kRows / 8 / WAVES, LX = S::kTokens / 8 / WAVES;  // direct loads per wave and chunk
   static_assert(S::kRows % (8 * WAVES) == 0 && S::kTokens % (8 * WAVES) == 0, "whole 8-row loads per wave");
@@ -447,9 +504,36 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
       __syncthreads();
     }
 
+    uint2* ex = reinterpret_cast<uint2*>(lds);   // [HALVES][kTokens][nh]: {magnitude bits, row | sign << 31}
+    if constexpr (RC != 0) {
+      // r is the constant RC: this wave's MTW tiles are kSeg whole hashes (for r = 256, half of the one hash)
+      constexpr int kSegTiles = RC / 32 < MTW ? RC / 32 : MTW;   // tiles per hash inside this wave
+      constexpr int kSeg = MTW / kSegTiles;                      // hashes (or hash parts) per wave
+      const int mhu = __builtin_amdgcn_readfirstlane(mh);
+      static_for<kSeg>([&](auto sc) {
+        constexpr int sg = decltype(sc)::value;
+        const int lh = RC == 256 ? 0 : mhu * kSeg + sg;          // hash of this segment inside the group (wave-uniform)
+        if (lh < nh) {
+          float bv[NTW];
+          int bid[NTW];
+          scan_hash_tiles<sg * kSegTiles, kSegTiles>(acc, bv, bid);
+          static_for<NTW>([&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            int bi = bid[u] + 4 * h + (RC == 256 ? mhu * 128 : 0);
+            bool neg;
+            const uint32_t best = join_lane_halves(bv[u], bi, neg);
+            if (HALVES == 1) {
+              b[u] = b[u] * (uint64_t)(2 * RC) + (uint64_t)(bi + (neg ? RC : 0));
+            } else if (h == 0) {
+              ex[((mh * S::kTokens) + g * NTW * 32 + u * 32 + n) * nh + lh] =
+                  make_uint2(best, (uint32_t)bi | (neg ? 0x80000000u : 0u));
+            }
+          });
+        }
+      });
+    } else {
     // Signed arg-max per hash over the rows this wave holds (tiles mh*MTW .. mh*MTW + MTW-1).  Same two-pass
     // integer scheme as hash_kernel's aligned epilogue.  With two halves the results are joined through LDS.
-    uint2* ex = reinterpret_cast<uint2*>(lds);   // [HALVES][kTokens][nh]: {magnitude bits, row | sign << 31}
     for (int lh = 0; lh < nh; ++lh) {
       const int lo = lh * r;
 #pragma unroll
@@ -515,6 +599,7 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
         }
       }
     }
+    }
     if (GATE) {
       // rows rows_h .. rows_h + E - 1 are gate logits: a lane holds 4 consecutive ones of its token per register quad
 #pragma unroll
@@ -546,11 +631,18 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
         for (int u = 0; u < NTW; ++u) {
           const int tok = g * NTW * 32 + u * 32 + n;
           for (int lh = 0; lh < nh; ++lh) {
-            const uint2 lo_half = ex[tok * nh + lh], hi_half = ex[(S::kTokens + tok) * nh + lh];
-            uint32_t code = lo_half.y;
-            // rows of the upper half are higher, so on equal magnitude the lower half wins unless it holds no row
-            if (hi_half.x > lo_half.x || (hi_half.x == lo_half.x && (hi_half.y & 0x7fffffffu) < (code & 0x7fffffffu)))
-              code = hi_half.y;
+            uint32_t code;
+            if constexpr (RC != 0 && RC != 256) {
+              // whole hashes per wave: hash lh was finished by the wave of half lh / (hashes per wave)
+              constexpr int kPerWave = MTW * 32 / RC;
+              code = ex[((lh / kPerWave) * S::kTokens + tok) * nh + lh].y;
+            } else {
+              const uint2 lo_half = ex[tok * nh + lh], hi_half = ex[(S::kTokens + tok) * nh + lh];
+              code = lo_half.y;
+              // rows of the upper half are higher, so on equal magnitude the lower half wins unless it holds no row
+              if (hi_half.x > lo_half.x || (hi_half.x == lo_half.x && (hi_half.y & 0x7fffffffu) < (code & 0x7fffffffu)))
+                code = hi_half.y;
+            }
             b[u] = b[u] * (uint64_t)(2 * r) + (uint64_t)((code & 0x7fffffffu) + ((code >> 31) ? (uint32_t)r : 0u));
           }
         }
@@ -566,13 +658,14 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
   }
 }
 
-template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX, bool GATE = false>
+template <typename DT, int MTW, int NTW, int GROUPS, int HALVES, int DR, int DX, bool GATE = false, int RC = 0>
 hipError_t launch_stream(const char* x, const char* R, uint64_t* bucket, int64_t T, int row_pieces, int L, int r, int hpg,
                          hipStream_t stream, const char* gate_w = nullptr, int E = 0, float* logits = nullptr) {
   using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
   static_assert(S::kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
   if ((GATE ? L * r + E : hpg * r) > S::kRows) return hipErrorInvalidValue;  // the instance must hold every row of a pass
-  auto kern = hash_stream_kernel<DT, MTW, NTW, GROUPS, HALVES, DR, DX, GATE>;
+  if (RC != 0 && r != RC) return hipErrorInvalidValue;                       // a compile-time r must be the real one
+  auto kern = hash_stream_kernel<DT, MTW, NTW, GROUPS, HALVES, DR, DX, GATE, RC>;
   static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
   if (!raised.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes);
@@ -629,21 +722,26 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
   // Widest groups on large inputs: the 4 x 2 tiling with the rows of R split between two waves (see hash_stream_kernel).
   // Measured at T = 65536, d = 1024, 256 rows: 42 us against 45 us with tokens coming from HBM, 47 us against
   // 43 us when the tokens are still in the last-level cache.
-  if (mt >= 7 && fast && T >= 256 * 256)
-    return launch_stream<DT, 4, 2, 4, 2, 1, 2>(x, R, bucket, T, row_pieces, L, r, hpg, stream);
+  if (mt >= 7 && fast && T >= 256 * 256) {
+#define LSHMOE_WIDE(RC) launch_stream<DT, 4, 2, 4, 2, 1, 2, false, RC>(x, R, bucket, T, row_pieces, L, r, hpg, stream)
+    return r == 64 ? LSHMOE_WIDE(64) : r == 128 ? LSHMOE_WIDE(128) : r == 256 ? LSHMOE_WIDE(256)
+         : r == 32 ? LSHMOE_WIDE(32) : LSHMOE_WIDE(0);
+#undef LSHMOE_WIDE
+  }
   // Few rows of R (mt <= 4): the kernel is bound by streaming the tokens.  From about 8k tokens on the streaming
   // kernel wins (measured per call: GPT shape 23.7 -> 18.9 us, Swin 12.7 -> 10.6, RoBERTa 13.1 -> 10.7): 128-token
   // workgroups of four waves with the tokens four chunks ahead once there are enough tokens for ~200 of them,
   // else 64-token workgroups of two waves three chunks ahead.
   if (fast && mt <= 4 && T >= 8192) {
     const bool big = T >= 24576;
-#define LSHMOE_STREAM(MT) \
-    (big ? launch_stream<DT, MT, 1, 4, 1, 3, 4>(x, R, bucket, T, row_pieces, L, r, hpg, stream) \
-         : launch_stream<DT, MT, 1, 2, 1, 2, 3>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
-    if (mt <= 1) return LSHMOE_STREAM(1);
-    if (mt == 2) return LSHMOE_STREAM(2);
-    if (mt == 3) return LSHMOE_STREAM(3);
-    return LSHMOE_STREAM(4);
+#define LSHMOE_STREAM(MT, RC) \
+    (big ? launch_stream<DT, MT, 1, 4, 1, 3, 4, false, RC>(x, R, bucket, T, row_pieces, L, r, hpg, stream) \
+         : launch_stream<DT, MT, 1, 2, 1, 2, 3, false, RC>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
+    // r = 32 and r = 64 (whole hashes per tile or per two tiles) take the arg-max with compile-time row ranges
+    if (mt <= 1) return r == 32 ? LSHMOE_STREAM(1, 32) : LSHMOE_STREAM(1, 0);
+    if (mt == 2) return r == 32 ? LSHMOE_STREAM(2, 32) : r == 64 ? LSHMOE_STREAM(2, 64) : LSHMOE_STREAM(2, 0);
+    if (mt == 3) return r == 32 ? LSHMOE_STREAM(3, 32) : LSHMOE_STREAM(3, 0);
+    return r == 32 ? LSHMOE_STREAM(4, 32) : r == 64 ? LSHMOE_STREAM(4, 64) : LSHMOE_STREAM(4, 0);
 #undef LSHMOE_STREAM
   }
   if (mt >= 5) {                           // 129..192 rows take the 6-tile instance, more the 8-tile one
