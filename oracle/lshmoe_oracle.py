@@ -20,9 +20,11 @@ identity / orthonormal closed forms, dict- and numpy.unique-based grouping,
 mass conservation, exact reconstruction for singleton buckets, the linear
 expert closed form, hand-worked gate-weighted combines (shared two-member
 clusters, unequal weights) and the weighted-sum identity over the unweighted
-rows, a hand-worked case of the row-scaled error metric; for the backward pass central finite differences of the
-forward functions of this file, its closed forms for one-member clusters and
-for an identity expert, and gradient mass conservation.  Absolute values of
+rows, a hand-worked case of the row-scaled error metric; for the backward pass
+central finite differences of the forward functions of this file (also through
+the gate-weighted combine, for tokens and for gate weights), its closed forms
+for one-member clusters and for an identity expert, a hand-worked combine
+gradient, and gradient mass conservation.  Absolute values of
 the whole path on the synthetic workloads have no printed counterpart in the
 paper: beyond those pins they are parity unpinned.
 """
@@ -256,6 +258,29 @@ def compress_backward_ref(grad_out: np.ndarray, grad_centroids: np.ndarray, grad
     else:
         per_a = widen(grad_out, dtype) + (h - widen(grad_expert_out, dtype)[s]) / n
     return narrow(per_a.reshape(T, k, -1).sum(axis=1), dtype)
+
+
+def combine_backward_ref(tokens: np.ndarray, centroids: np.ndarray, expert_out: np.ndarray, seg_of: np.ndarray,
+                         k: int, dtype: str, gate_weight: np.ndarray, grad_out: np.ndarray,
+                         no_residual: bool = False):
+    """Backward of the gate-weighted combine of restore_ref(gate_weight=...) (Eq. 2 with gate weights over
+    Eq. 4 / Eq. 5):  out[t] = sum_j w[t, j] * Y[t*k + j]  is linear in the weights and in the restored rows, so
+        dL/dw[t, j]   = < grad_out[t, :], Y[t*k + j, :] >          (the gate's gradient; float64, not rounded)
+        dL/dY[t*k+j]  = w[t, j] * grad_out[t, :]                    (rounded once to the storage type)
+    with Y[a] = E(c_s) + (x_a - c_s) (or E(c_s) without the residual) evaluated, as in the forward, from the stored
+    centroids and never rounded itself.  dL/dY is what restore_backward_ref and compress_backward_ref take as
+    their grad_out.  grad_out is [T, d] in storage form, gate_weight [T, k]."""
+    s = seg_of.astype(np.int64)
+    N = s.size
+    T = N // k
+    y = widen(expert_out, dtype)[s]
+    if not no_residual:
+        y = y + (widen(tokens, dtype)[np.arange(N) // k] - widen(centroids, dtype)[s])
+    g = widen(grad_out, dtype)                        # [T, d]
+    grad_w = np.einsum("td,tkd->tk", g, y.reshape(T, k, -1))
+    w = gate_weight.astype(np.float64).reshape(T, k, 1)
+    grad_y = (w * g[:, None, :]).reshape(N, -1)
+    return grad_w, narrow(grad_y, dtype)
 
 
 # --------------------------------------------------------------------------
