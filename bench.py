@@ -437,6 +437,24 @@ def main():
             "pair_ms": float(np.mean([e0.elapsed_time(e2) for e0, _, e2 in evb[5:]])),
             "decompress_backward_ms": seg_ms, "decompress_backward_gbs": seg_bytes / (seg_ms * 1e-3) / 1e9,
             "compress_backward_ms": gtok_ms, "compress_backward_gbs": gtok_bytes / (gtok_ms * 1e-3) / 1e9}
+    # supplementary: backward of the fused combine (gate-weight gradient and the row gradients w * dL/dout)
+    go = torch.randn((T, d), device="cuda").to(tdt)
+    gwo = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    gyo = torch.empty((T, k, d), dtype=tdt, device="cuda")
+    evc = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(K, 50))]
+    for i, (e0, e1) in enumerate(evc):
+        c = i % copies
+        e0.record()
+        lsh.lshmoe_decompress_combine_backward(xs[c], outs[c].centroids, ecs[c], outs[c].seg_of, outs[c].seg_offsets, gw,
+                                               go, gwo, gyo)
+        e1.record()
+    torch.cuda.synchronize()
+    if len(evc) > 5:
+        cb_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evc[5:]]))
+        cb_bytes = (S + 2 * T + n_multi_assign + n_multi_seg + N) * row + 12 * N + 4 * (S + 1)
+        result["supplementary_combine_backward"] = {"ms": cb_ms, "algorithmic_bytes": cb_bytes,
+                                                    "achieved_gbs": cb_bytes / (cb_ms * 1e-3) / 1e9}
+    del go, gwo, gyo
     if args.peaks:
         mp = measured_peaks()
         result["measured_peaks"] = mp

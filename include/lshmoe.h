@@ -12,6 +12,7 @@
  *   lshmoe_hash_gate            lshmoe_hash that also returns the gate's projection of the tokens (Eq. 1)
  *   lshmoe_decompress_combine   lshmoe_decompress fused with the gate-weighted sum over a token's experts (Eq. 2)
  *   lshmoe_decompress_backward, lshmoe_compress_backward   gradients through the two calls above
+ *   lshmoe_decompress_combine_backward                      gradients of the fused combine (gate weights and rows)
  *   lshmoe_compress_static      lshmoe_compress on scratch memory built into the library (allocates nothing)
  *
  * Notation: T tokens of dimension d; every token is routed to k distinct
@@ -269,6 +270,33 @@ lshmoe_status lshmoe_decompress_combine(const void* tokens, const void* centroid
  * payload of the backward all-to-all); the experts' backward returns dL/dc for
  * their inputs; lshmoe_compress_backward turns both into dL/dx.
  */
+
+/*
+ * Backward of lshmoe_decompress_combine (Eq. 2 with gate weights over Eq. 4 / Eq. 5).  The fused output
+ *     out[t, :] = sum_{j<k} w[t][j] * Y[t][j],   Y[t][j] = expert_out[s_j] + (tokens[t] - centroids[s_j])
+ * is linear in the weights and in the restored rows, so for grad_out = dL/dout:
+ *     grad_gate_weight[t][j] = < grad_out[t, :], Y[t][j] >     binary32; the gradient of the gate's weights
+ *     grad_rows[t][j][:]     = w[t][j] * grad_out[t, :]         dtype, rounded once; dL/dY in assignment order
+ * The restored rows are formed as in the forward call (from the stored centroids; without the residual term
+ * under LSHMOE_FLAG_NO_RESIDUAL) and are not stored.  grad_rows is what lshmoe_decompress_backward and
+ * lshmoe_compress_backward take as grad_out, so the three calls in this order give dL/dEC and dL/dx of a layer
+ * that uses the fused combine.  The dot products are accumulated in binary32 (each lane its pieces in ascending
+ * order, then the lanes pairwise): reproducible bit for bit.
+ *
+ *   grad_out          [T, d]     in   dtype
+ *   gate_weight       [T, k]     in   binary32
+ *   grad_gate_weight  [T, k]     out  binary32
+ *   grad_rows         [T, k, d]  out  dtype
+ *   other arguments as for lshmoe_decompress_combine.
+ *
+ * Errors: NULL pointer (seg_offsets excepted); T, d, k <= 0; N >= 2^30 or N * d too large for one launch
+ * (UNSUPPORTED); unknown flag bits (UNSUPPORTED); row size not a multiple of 16 bytes (UNSUPPORTED); launch failure (HIP).
+ */
+lshmoe_status lshmoe_decompress_combine_backward(const void* tokens, const void* centroids, const void* expert_out,
+                                                 const int32_t* seg_of, const int32_t* seg_offsets,
+                                                 const float* gate_weight, const void* grad_out,
+                                                 int64_t T, int32_t d, int32_t k, lshmoe_dtype dtype, uint32_t flags,
+                                                 float* grad_gate_weight, void* grad_rows, void* stream);
 
 /* Bytes of device scratch lshmoe_decompress_backward needs (host only).  A
  * workspace sized by lshmoe_workspace_bytes for the same T, d, k is also

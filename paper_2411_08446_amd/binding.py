@@ -22,7 +22,7 @@ LSHMOE_ERR_HIP = 5
 LSHMOE_F32 = 0
 LSHMOE_BF16 = 1
 LSHMOE_FLAG_NO_RESIDUAL = 1
-ABI_VERSION = 5   # of include/lshmoe.h as this binding declares it
+ABI_VERSION = 6   # of include/lshmoe.h as this binding declares it
 
 
 class LshmoeError(RuntimeError):
@@ -70,6 +70,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.lshmoe_decompress.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
     lib.lshmoe_decompress_combine.restype = ctypes.c_int
     lib.lshmoe_decompress_combine.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp]
+    lib.lshmoe_decompress_combine_backward.restype = ctypes.c_int
+    lib.lshmoe_decompress_combine_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, ctypes.c_int, u32, vp, vp, vp]
     lib.lshmoe_backward_workspace_bytes.restype = ctypes.c_int
     lib.lshmoe_backward_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
     lib.lshmoe_decompress_backward.restype = ctypes.c_int
@@ -240,6 +242,24 @@ def lshmoe_decompress_combine(tokens: torch.Tensor, centroids: torch.Tensor, exp
         _ptr(tokens), _ptr(centroids), _ptr(expert_out), _ptr(seg_of, torch.int32),
         _ptr(seg_offsets, torch.int32), _ptr(gate_weight, torch.float32), T, d, k, _dtype_code(tokens), flags,
         _ptr(out), _stream(stream)))
+
+
+def lshmoe_decompress_combine_backward(tokens: torch.Tensor, centroids: torch.Tensor, expert_out: torch.Tensor,
+                                       seg_of: torch.Tensor, seg_offsets, gate_weight: torch.Tensor,
+                                       grad_out: torch.Tensor, grad_gate_weight: torch.Tensor, grad_rows: torch.Tensor,
+                                       flags: int = 0, stream=None) -> None:
+    """grad_out [T, d] -> grad_gate_weight [T, k] (binary32) and grad_rows [T, k, d] = w[t, j] * grad_out[t]."""
+    T, d = tokens.shape
+    k = gate_weight.shape[1]
+    if (gate_weight.shape[0] != T or seg_of.numel() != T * k or grad_out.shape != (T, d) or grad_out.dtype != tokens.dtype
+            or grad_gate_weight.shape != (T, k) or grad_rows.numel() != T * k * d or grad_rows.dtype != tokens.dtype):
+        raise ValueError("gate_weight and grad_gate_weight must be [T, k], grad_out [T, d] and grad_rows [T, k, d]")
+    if centroids.dtype != tokens.dtype or expert_out.dtype != tokens.dtype:
+        raise TypeError("centroids and expert_out must have the token dtype")
+    _check(load_library().lshmoe_decompress_combine_backward(
+        _ptr(tokens), _ptr(centroids), _ptr(expert_out), _ptr(seg_of, torch.int32), _ptr(seg_offsets, torch.int32),
+        _ptr(gate_weight, torch.float32), _ptr(grad_out), T, d, k, _dtype_code(tokens), flags,
+        _ptr(grad_gate_weight, torch.float32), _ptr(grad_rows), _stream(stream)))
 
 
 def lshmoe_backward_workspace_bytes(T: int, d: int, k: int, dtype_code: int) -> int:

@@ -129,7 +129,7 @@ const char* lshmoe_status_string(int status) {
 
 const char* lshmoe_last_error(void) { return g_err; }
 
-int lshmoe_abi_version(void) { return 5; }
+int lshmoe_abi_version(void) { return 6; }
 
 lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E, int32_t L, int32_t r,
                                      lshmoe_dtype dtype, size_t* out_bytes) {
@@ -255,6 +255,22 @@ lshmoe_status lshmoe_decompress_combine(const void* tokens, const void* centroid
   hipError_t e = lshmoe::launch_restore_combine(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, out, T,
                                                 k, d, dtype == LSHMOE_BF16, flags, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail("restore-combine launch", e);
+  return ok();
+}
+
+lshmoe_status lshmoe_decompress_combine_backward(const void* tokens, const void* centroids, const void* expert_out,
+                                                 const int32_t* seg_of, const int32_t* seg_offsets,
+                                                 const float* gate_weight, const void* grad_out, int64_t T, int32_t d,
+                                                 int32_t k, lshmoe_dtype dtype, uint32_t flags, float* grad_gate_weight,
+                                                 void* grad_rows, void* stream) {
+  if (!tokens || !centroids || !expert_out || !seg_of || !gate_weight || !grad_out || !grad_gate_weight || !grad_rows)
+    return fail(LSHMOE_ERR_NULL, "an input or output pointer is NULL");
+  if (flags & ~(uint32_t)LSHMOE_FLAG_NO_RESIDUAL) return fail(LSHMOE_ERR_UNSUPPORTED, "unknown flag bits 0x%x", flags);
+  if (lshmoe_status st = check_rows_shape(T, d, k, (int)dtype)) return st;
+  hipError_t e = lshmoe::launch_combine_backward(tokens, centroids, expert_out, seg_of, seg_offsets, gate_weight, grad_out,
+                                                 grad_gate_weight, grad_rows, T, k, d, dtype == LSHMOE_BF16, flags,
+                                                 (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("combine backward launch", e);
   return ok();
 }
 

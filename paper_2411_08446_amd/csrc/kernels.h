@@ -86,4 +86,10 @@ hipError_t launch_grad_tokens(const void* grad_out, const void* grad_centroids, 
                               const int32_t* seg_of, const int32_t* seg_offsets, void* grad_tokens, int64_t T, int k,
                               int d, bool bf16, uint32_t flags, hipStream_t stream);
 
+// Backward of the fused restore + combine: grad_w [T][k] binary32, grad_rows [T][k][d] in the storage type.
+hipError_t launch_combine_backward(const void* tokens, const void* centroids, const void* expert_out,
+                                   const int32_t* seg_of, const int32_t* seg_offsets, const float* gate_weight,
+                                   const void* grad_out, float* grad_w, void* grad_rows, int64_t T, int k, int d, bool bf16,
+                                   uint32_t flags, hipStream_t stream);
+
 }  // namespace lshmoe

@@ -173,7 +173,34 @@ def check_combine(run: GpuRun, tokens: np.ndarray, gate_weight: np.ndarray, k: i
     seg_of = run.out.seg_of.cpu().numpy()
     ref = oracle.restore_ref(tokens, run.centroids, run.expert_out, seg_of, k, dtype, no_residual=bool(flags & 1),
                              gate_weight=gate_weight)
-    return assert_rows_close(got, ref, dtype, "restore+combine")
+    worst = assert_rows_close(got, ref, dtype, "restore+combine")
+
+    # backward of the fused call on a seeded output gradient: the gate-weight gradient within the binary32
+    # accumulation bound of its dot products, the row gradients bit for bit (one exact product, rounded once)
+    from workloads import synth
+    rng = np.random.default_rng(1000 + T + 7 * k + flags)
+    go = synth.f32_to_storage(rng.standard_normal((T, d)).astype(np.float32), dtype)
+    got_t = to_device(go, dtype)
+    gw_t = torch.full((T, k), float("nan"), dtype=torch.float32, device="cuda")
+    gy_t = torch.full((T, k, d), float("nan"), dtype=xt.dtype, device="cuda")
+    lsh.lshmoe_decompress_combine_backward(xt, run.out.centroids, ect, run.out.seg_of,
+                                           run.out.seg_offsets if use_seg_offsets else None, wt, got_t, gw_t, gy_t,
+                                           flags=flags)
+    torch.cuda.synchronize()
+    gw_ref, gy_ref = oracle.combine_backward_ref(tokens, run.centroids, run.expert_out, seg_of, k, dtype, gate_weight,
+                                                 go, no_residual=bool(flags & 1))
+    assert np.array_equal(to_storage(gy_t.view(T * k, d), dtype), gy_ref), "row gradients of the combine: w * dL/dout, rounded once"
+    # |error| <= (d / 64 + 24) 2^-24 sum_i |g_i| (|EC_i| + |x_i - c_i|): a lane adds its share of the row in order,
+    # then six pairwise steps; Y_i itself is a rounded binary32 sum of the two terms
+    y_abs = np.abs(oracle.widen(run.expert_out, dtype)[seg_of])
+    if not (flags & 1):
+        y_abs = y_abs + np.abs(oracle.widen(tokens, dtype)[np.arange(T * k) // k] - oracle.widen(run.centroids, dtype)[seg_of])
+    bound = (d / 64 + 24) * 2.0 ** -24 * np.einsum("td,tkd->tk", np.abs(oracle.widen(go, dtype)), y_abs.reshape(T, k, d))
+    err = np.abs(gw_t.cpu().numpy().astype(np.float64) - gw_ref)
+    assert np.all(err <= bound + 1e-300), "gate-weight gradient off by %.3g x its accumulation bound" % float((err / np.maximum(bound, 1e-300)).max())
+    WORST[("gate-weight gradient / bound", dtype)] = max(WORST.get(("gate-weight gradient / bound", dtype), 0.0),
+                                                         float((err / np.maximum(bound, 1e-300)).max()))
+    return worst
 
 
 def check_backward(run: GpuRun, T: int, d: int, k: int, dtype: str, seed: int, flags: int = 0):

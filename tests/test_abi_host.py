@@ -31,7 +31,7 @@ def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
     assert {"lshmoe_hash", "lshmoe_compress", "lshmoe_decompress", "lshmoe_decompress_combine", "lshmoe_workspace_bytes",
             "lshmoe_backward_workspace_bytes", "lshmoe_decompress_backward", "lshmoe_compress_backward", "lshmoe_hash_gate",
-            "lshmoe_status_string", "lshmoe_last_error", "lshmoe_abi_version", "lshmoe_compress_static"} <= set(names)
+            "lshmoe_status_string", "lshmoe_last_error", "lshmoe_abi_version", "lshmoe_compress_static", "lshmoe_decompress_combine_backward"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

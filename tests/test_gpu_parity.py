@@ -332,7 +332,7 @@ def test_fused_gate_weighted_combine_named(H, name, T):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("T,d,k,E", [(700, 24, 3, 5), (333, 512, 1, 4), (50, 8, 4, 4)])
+@pytest.mark.parametrize("T,d,k,E", [(700, 24, 3, 5), (333, 512, 1, 4), (50, 8, 4, 4), (61, 16, 6, 7), (130, 1024, 5, 9)])
 def test_fused_gate_weighted_combine_shapes(H, dtype, T, d, k, E):
     tokens, rot, expert = _rand_inputs(77 + T, T, d, k, E, 2, 8, dtype, centers=max(2, T // 8))
     gw = np.random.default_rng(T).random((T, k)).astype(np.float32) + 0.1
