@@ -26,7 +26,11 @@ the gate-weighted combine, for tokens and for gate weights), its closed forms
 for one-member clusters and for an identity expert, a hand-worked combine
 gradient, and gradient mass conservation.  Absolute values of
 the whole path on the synthetic workloads have no printed counterpart in the
-paper: beyond those pins they are parity unpinned.
+paper: beyond those pins they are parity unpinned.  sphere_hash_ref follows a
+reading of a hash family that the paper only names (Section 4.5): it is pinned
+to its own definition (exact integer brute force, translation invariance,
+radius monotonicity, the hyperplane limit, bit order by hand) and stays
+parity unpinned against the paper.
 """
 from __future__ import annotations
 
@@ -120,6 +124,38 @@ def gate_logits_ref(tokens: np.ndarray, gate_w: np.ndarray, dtype: str) -> np.nd
     whose form the paper leaves open): logits[t, e] = <gate_w[e, :], x_t>,
     in binary64, not rounded.  tokens [T, d], gate_w [E, d] in storage form."""
     return widen(tokens, dtype) @ widen(gate_w, dtype).T
+
+
+def sphere_hash_ref(tokens: np.ndarray, pivots: np.ndarray, radius_sq: np.ndarray, dtype: str):
+    """Spherical hashing, the alternative hash family of the ablation in Section 4.5 ("SP").  The paper names
+    it without defining it; the reading taken here is the hypersphere-based binary code of spherical hashing:
+    hash function l is a sphere with centre pivots[l] and squared radius radius_sq[l], and
+        bit_l(x) = 1  if  ||x - p_l||^2 <= radius_sq[l]  (inside or on the sphere),  else 0.
+    The B bits form the bucket id, bit 0 most significant (as the digits of the cross-polytope hash).  Far pivots
+    with large radii make the spheres locally flat, which is how the family contains hyperplane hashing.
+
+    tokens [T, d], pivots [B, d] in storage form, radius_sq [B] float (any real values, B <= 63).
+    Returns (bucket uint64 [T], bit uint8 [T, B], margin float64 [T, B]) with
+    margin = | ||x - p_l||^2 - radius_sq[l] | / max(|radius_sq[l]|, ||x - p_l||^2): how far, relatively, the token is
+    from the decision surface, so that a lower-precision implementation can recognise borderline bits."""
+    B, d = pivots.shape
+    T = tokens.shape[0]
+    assert tokens.shape == (T, d) and radius_sq.shape == (B,) and 1 <= B <= 63
+    x = widen(tokens, dtype)
+    p = widen(pivots, dtype)
+    t2 = np.asarray(radius_sq, dtype=np.float64)
+    bit = np.empty((T, B), np.uint8)
+    margin = np.empty((T, B), np.float64)
+    for l in range(B):
+        diff = x - p[l]                              # [T, d]
+        dist2 = (diff * diff).sum(axis=1)
+        bit[:, l] = dist2 <= t2[l]
+        scale = np.maximum(np.abs(t2[l]), dist2)
+        margin[:, l] = np.abs(dist2 - t2[l]) / np.where(scale > 0.0, scale, 1.0)
+    bucket = np.zeros(T, np.uint64)
+    for l in range(B):
+        bucket = bucket * np.uint64(2) + bit[:, l].astype(np.uint64)
+    return bucket, bit, margin
 
 
 def combine_codes(code: np.ndarray, r: int) -> np.ndarray:
