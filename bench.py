@@ -437,6 +437,22 @@ def main():
             "pair_ms": float(np.mean([e0.elapsed_time(e2) for e0, _, e2 in evb[5:]])),
             "decompress_backward_ms": seg_ms, "decompress_backward_gbs": seg_bytes / (seg_ms * 1e-3) / 1e9,
             "compress_backward_ms": gtok_ms, "compress_backward_gbs": gtok_bytes / (gtok_ms * 1e-3) / 1e9}
+    # supplementary: the spherical hash family (Section 4.5), 32 spheres with balanced radii, on the same tokens
+    sb = 32
+    piv = (torch.randn((sb, d), device="cuda")).to(tdt)
+    rsq = torch.full((sb,), float(d * (2.0 + cfg.sigma ** 2)), dtype=torch.float32, device="cuda")
+    sbucket = torch.empty(T, dtype=torch.int64, device="cuda")
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(K, 50))]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        lsh.lshmoe_hash_sphere(xs[i % copies], piv, rsq, sbucket)
+        e1.record()
+    torch.cuda.synchronize()
+    if len(evs) > 5:
+        sp_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs[5:]]))
+        result["supplementary_sphere_hash"] = {"spheres": sb, "ms": sp_ms, "token_read_gbs": T * row / (sp_ms * 1e-3) / 1e9,
+                                               "distinct_codes": int(torch.unique(sbucket).numel())}
+    del piv, rsq, sbucket
     # supplementary: backward of the fused combine (gate-weight gradient and the row gradients w * dL/dout)
     go = torch.randn((T, d), device="cuda").to(tdt)
     gwo = torch.empty((T, k), dtype=torch.float32, device="cuda")

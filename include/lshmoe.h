@@ -9,6 +9,7 @@
  *                      replace every cluster by its centroid        (Alg. 1, the two nested loops)
  *   lshmoe_decompress  give every token the expert output of its
  *                      centroid plus the token's residual           (Eq. 4, Eq. 5)
+ *   lshmoe_hash_sphere          the spherical hash family of the ablation (Section 4.5), one bit per sphere
  *   lshmoe_hash_gate            lshmoe_hash that also returns the gate's projection of the tokens (Eq. 1)
  *   lshmoe_decompress_combine   lshmoe_decompress fused with the gate-weighted sum over a token's experts (Eq. 2)
  *   lshmoe_decompress_backward, lshmoe_compress_backward   gradients through the two calls above
@@ -123,6 +124,32 @@ lshmoe_status lshmoe_workspace_bytes(int64_t T, int32_t d, int32_t k, int32_t E,
 lshmoe_status lshmoe_hash(const void* tokens, const void* rot,
                           int64_t T, int32_t d, int32_t L, int32_t r, lshmoe_dtype dtype,
                           uint64_t* bucket, void* stream);
+
+/*
+ * Spherical hash: the alternative hash family of the ablation in Section 4.5 ("SP"; Section 3.2 lists it among the
+ * LSH algorithms that were tried).  The paper names the family without defining it; this entry point takes it as the
+ * hypersphere-based binary code of spherical hashing: sphere l has the centre pivots[l, :] and the squared radius
+ * radius_sq[l], and
+ *     bit_l(x) = 1  if  |x - p_l|^2 <= radius_sq[l]  (inside or on the sphere),  else 0;
+ *     bucket[t] = sum_l bit_l(x_t) * 2^(B-1-l)        (bit 0 most significant).
+ * Pivots far away with large radii give locally flat spheres, i.e. hyperplane hashing.  How the spheres are chosen
+ * is the caller's business.  The bucket ids feed lshmoe_compress like those of lshmoe_hash; its L and r only have to
+ * bound them, (2r)^L >= 2^B: for example r = 2 and L = ceil(B / 2).
+ *
+ *   tokens    [T, d]  in   dtype
+ *   pivots    [B, d]  in   dtype
+ *   radius_sq [B]     in   binary32 (any real values; a negative one leaves its sphere empty)
+ *   bucket    [T]     out  uint64
+ *
+ * |x - p|^2 is evaluated as |x|^2 - 2 <p, x> + |p|^2 in binary32 (the dot product on the matrix cores), so a token
+ * whose squared distance is within about 1e-4 relative of the squared radius may get the other bit than exact
+ * arithmetic gives.
+ * Errors: NULL pointer; T, d, B <= 0; B > 63 (UNSUPPORTED); d*sizeof(element) not a multiple of 16 (UNSUPPORTED);
+ * T >= 2^30 (UNSUPPORTED); launch failure (HIP).
+ */
+lshmoe_status lshmoe_hash_sphere(const void* tokens, const void* pivots, const float* radius_sq,
+                                 int64_t T, int32_t d, int32_t B, lshmoe_dtype dtype,
+                                 uint64_t* bucket, void* stream);
 
 /*
  * lshmoe_hash fused with the linear part of a learned gate (the gating network G of Section 2.1, Eq. 1; the

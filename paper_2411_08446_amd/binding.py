@@ -58,6 +58,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.lshmoe_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
     lib.lshmoe_hash.restype = ctypes.c_int
     lib.lshmoe_hash.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, vp, vp]
+    lib.lshmoe_hash_sphere.restype = ctypes.c_int
+    lib.lshmoe_hash_sphere.argtypes = [vp, vp, vp, i64, i32, i32, ctypes.c_int, vp, vp]
     lib.lshmoe_hash_gate.restype = ctypes.c_int
     lib.lshmoe_hash_gate.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, ctypes.c_int, vp, vp, vp]
     lib.lshmoe_compress.restype = ctypes.c_int
@@ -127,6 +129,17 @@ def lshmoe_hash(tokens: torch.Tensor, rot: torch.Tensor, bucket: torch.Tensor, s
         raise ValueError("shape/dtype mismatch between tokens, rot and bucket")
     _check(load_library().lshmoe_hash(_ptr(tokens), _ptr(rot), T, d, L, r, _dtype_code(tokens),
                                       _ptr(bucket, torch.int64), _stream(stream)))
+
+
+def lshmoe_hash_sphere(tokens: torch.Tensor, pivots: torch.Tensor, radius_sq: torch.Tensor, bucket: torch.Tensor,
+                       stream=None) -> None:
+    """tokens [T, d], pivots [B, d] (same dtype), radius_sq [B] (float32) -> bucket [T]: one bit per sphere."""
+    T, d = tokens.shape
+    B, d2 = pivots.shape
+    if d2 != d or pivots.dtype != tokens.dtype or radius_sq.numel() != B or bucket.numel() != T:
+        raise ValueError("shape/dtype mismatch between tokens, pivots, radius_sq and bucket")
+    _check(load_library().lshmoe_hash_sphere(_ptr(tokens), _ptr(pivots), _ptr(radius_sq, torch.float32), T, d, B,
+                                             _dtype_code(tokens), _ptr(bucket, torch.int64), _stream(stream)))
 
 
 def lshmoe_hash_gate(tokens: torch.Tensor, rot: torch.Tensor, gate_w: torch.Tensor, bucket: torch.Tensor,

@@ -153,6 +153,20 @@ lshmoe_status lshmoe_hash(const void* tokens, const void* rot, int64_t T, int32_
   return ok();
 }
 
+lshmoe_status lshmoe_hash_sphere(const void* tokens, const void* pivots, const float* radius_sq, int64_t T, int32_t d,
+                                 int32_t B, lshmoe_dtype dtype, uint64_t* bucket, void* stream) {
+  if (!tokens || !pivots || !radius_sq || !bucket)
+    return fail(LSHMOE_ERR_NULL, "tokens, pivots, radius_sq and bucket must be non-NULL");
+  if (T <= 0 || d <= 0 || B <= 0) return fail(LSHMOE_ERR_SHAPE, "T, d and B must be positive (T=%lld, d=%d, B=%d)", (long long)T, d, B);
+  if (B > 63) return fail(LSHMOE_ERR_UNSUPPORTED, "B = %d spheres; the code is one bit per sphere and the limit is 63", B);
+  if (lshmoe_status st = check_row(d, (int)dtype)) return st;
+  if (T >= kMaxAssignments) return fail(LSHMOE_ERR_UNSUPPORTED, "T = %lld tokens; the limit is 2^30 - 1", (long long)T);
+  hipError_t e = lshmoe::launch_hash_sphere(tokens, pivots, radius_sq, T, d, B, dtype == LSHMOE_BF16, bucket,
+                                            (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail("spherical hash launch", e);
+  return ok();
+}
+
 lshmoe_status lshmoe_hash_gate(const void* tokens, const void* rot, const void* gate_w, int64_t T, int32_t d, int32_t L,
                                int32_t r, int32_t E, lshmoe_dtype dtype, uint64_t* bucket, float* logits, void* stream) {
   if (!tokens || !rot || !gate_w || !bucket || !logits)

@@ -114,10 +114,23 @@ __device__ __forceinline__ uint32_t join_lane_halves(float bv, int& bi, bool& ne
   return best;
 }
 
-template <typename DT, int MT, int NTK, int XDEPTH, int WAVES, int OCC, bool ALIGNED8, bool KTAIL>
+// Sum of the squares of the elements of one 16-byte piece, added to acc in element order.
+template <typename DT> __device__ __forceinline__ float add_squares(const uint4& q, float acc) {
+  float v[Piece<DT>::kElems];
+  Piece<DT>::widen(q, v);
+#pragma unroll
+  for (int i = 0; i < Piece<DT>::kElems; ++i) acc = fmaf(v[i], v[i], acc);
+  return acc;
+}
+
+// SPHERE: the rows of `rot` are the pivots of r spheres (L = 1, one pass) and the code is one bit per sphere instead
+// of an arg-max: bit i = [ |x|^2 - 2 <p_i, x> + |p_i|^2 <= radius_sq[i] ], bit 0 most significant.  The dot products
+// are the same MFMA product; |x|^2 is gathered from the token pieces a lane feeds to the MFMAs (the two lane halves
+// hold the two halves of every chunk) and |p_i|^2 from the pieces a thread stages, all in binary32.
+template <typename DT, int MT, int NTK, int XDEPTH, int WAVES, int OCC, bool ALIGNED8, bool KTAIL, bool SPHERE = false>
 __global__ __launch_bounds__(WAVES * 64, OCC) void hash_kernel(const char* __restrict__ tokens, const char* __restrict__ rot,
                                                    uint64_t* __restrict__ bucket, uint32_t T, int row_pieces, int L,
-                                                   int r, int hpg) {
+                                                   int r, int hpg, const float* __restrict__ radius_sq = nullptr) {
   constexpr int RA = MT * 32;              // rows of R staged per chunk
   constexpr int SLOTS = RA * kPieces;      // 16-byte slots per LDS buffer
   extern __shared__ uint4 lds[];           // [2][SLOTS]
@@ -167,10 +180,18 @@ __global__ __launch_bounds__(WAVES * 64, OCC) void hash_kernel(const char* __res
       for (int i = 0; i < LA; ++i)
         stage[i] = in_row ? *reinterpret_cast<const uint4*>(a_base + off_a[i]) : make_uint4(0, 0, 0, 0);
     };
+    float pn[LA], nx2[NTK];                // SPHERE: partial |p|^2 of the rows this thread stages, partial |x|^2
+#pragma unroll
+    for (int i = 0; i < LA; ++i) pn[i] = 0.0f;
+#pragma unroll
+    for (int u = 0; u < NTK; ++u) nx2[u] = 0.0f;
     auto store_r = [&](int buf) {
       uint4* dst = lds + buf * SLOTS + st_slot;
 #pragma unroll
-      for (int i = 0; i < LA; ++i) dst[i * TH] = stage[i];
+      for (int i = 0; i < LA; ++i) {
+        dst[i * TH] = stage[i];
+        if (SPHERE) pn[i] = add_squares<DT>(stage[i], pn[i]);
+      }
     };
     uint4 xr[XDEPTH][NTK][kSteps];
     auto load_x = [&](int chunk, uint4 (&dst)[NTK][kSteps]) {
@@ -210,6 +231,12 @@ __global__ __launch_bounds__(WAVES * 64, OCC) void hash_kernel(const char* __res
         if (more) load_r(c + 1);
         if (c + XDEPTH - 1 < nchunks) load_x(c + XDEPTH - 1, xr[(j + XDEPTH - 1) % XDEPTH]);
         const uint4* buf = lds + (c & 1) * SLOTS;
+        if (SPHERE) {
+#pragma unroll
+          for (int u = 0; u < NTK; ++u)
+#pragma unroll
+            for (int st = 0; st < kSteps; ++st) nx2[u] = add_squares<DT>(xr[j][u][st], nx2[u]);
+        }
         // A fragments go through a small ring: the LDS read of (step, tile) i + kAhead is issued before the
         // MFMAs of (step, tile) i, and the scheduler is told to keep that order
         constexpr int kAhead = 3, kRing = 4, kFrags = kSteps * MT;
@@ -230,6 +257,39 @@ __global__ __launch_bounds__(WAVES * 64, OCC) void hash_kernel(const char* __res
       }
     }
 
+    if (SPHERE) {
+      // |p_i|^2: the 8 threads that staged the 8 pieces of a row sit in 8 consecutive lanes
+      float* pn2 = reinterpret_cast<float*>(lds);   // [RA]; every wave is past the last chunk's closing barrier
+#pragma unroll
+      for (int i = 0; i < LA; ++i) {
+        float v = pn[i];
+        v += __shfl_xor(v, 1, 64);
+        v += __shfl_xor(v, 2, 64);
+        v += __shfl_xor(v, 4, 64);
+        if (lp == 0) pn2[r0 + i * RS] = v;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < NTK; ++u) {
+        const float xx = nx2[u] + __shfl_xor(nx2[u], 32, 64);
+        uint64_t bits = 0;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const int row = t * 32 + 8 * (j >> 2) + 4 * h + (j & 3);
+            if (row < r) {
+              const float dist2 = (xx - 2.0f * acc[t][u][j]) + pn2[row];
+              if (dist2 <= radius_sq[row]) bits |= 1ull << (r - 1 - row);
+            }
+          }
+        }
+        const uint32_t lo32 = (uint32_t)bits, hi32 = (uint32_t)(bits >> 32);
+        bits |= (uint64_t)(uint32_t)__shfl_xor((int)lo32, 32, 64) | ((uint64_t)(uint32_t)__shfl_xor((int)hi32, 32, 64) << 32);
+        b[u] = bits;
+      }
+      continue;   // one pass (hpg = L = 1)
+    }
     // signed arg-max per hash of the group, from the accumulators
 #pragma unroll
     for (int u = 0; u < NTK; ++u) {
@@ -695,7 +755,8 @@ hipError_t launch_one(const char* x, const char* R, uint64_t* bucket, int64_t T,
     }
   }
   const dim3 grid((uint32_t)((T + kBlockTokens - 1) / kBlockTokens)), block(WAVES * 64);
-  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg);
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, x, R, bucket, (uint32_t)T, row_pieces, L, r, hpg,
+                     (const float*)nullptr);
   return hipGetLastError();
 }
 
@@ -760,7 +821,33 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
 #undef LSHMOE_HASH
 }
 
+// Spherical hash: B spheres (rows of `pivots`), one or two 32-row tiles, tokens straight into registers.
+template <typename DT>
+hipError_t launch_sphere_typed(const void* tokens, const void* pivots, const float* radius_sq, int64_t T, int d, int B,
+                               uint64_t* bucket, hipStream_t stream) {
+  if (B < 1 || B > 63) return hipErrorInvalidValue;
+  const int row_pieces = (int)((size_t)d * ItemSize<DT>::value / 16);
+  constexpr int kWaves = 4, kBlockTokens = kWaves * 32;
+  const dim3 grid((uint32_t)((T + kBlockTokens - 1) / kBlockTokens)), block(kWaves * 64);
+  if (B <= 32) {
+    constexpr size_t lds_bytes = (size_t)2 * 32 * kPieces * 16;
+    hipLaunchKernelGGL((hash_kernel<DT, 1, 1, 4, kWaves, 2, false, true, true>), grid, block, lds_bytes, stream,
+                       (const char*)tokens, (const char*)pivots, bucket, (uint32_t)T, row_pieces, 1, B, 1, radius_sq);
+  } else {
+    constexpr size_t lds_bytes = (size_t)2 * 64 * kPieces * 16;
+    hipLaunchKernelGGL((hash_kernel<DT, 2, 1, 4, kWaves, 2, false, true, true>), grid, block, lds_bytes, stream,
+                       (const char*)tokens, (const char*)pivots, bucket, (uint32_t)T, row_pieces, 1, B, 1, radius_sq);
+  }
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_hash_sphere(const void* tokens, const void* pivots, const float* radius_sq, int64_t T, int d, int B,
+                              bool bf16, uint64_t* bucket, hipStream_t stream) {
+  return bf16 ? launch_sphere_typed<BF16>(tokens, pivots, radius_sq, T, d, B, bucket, stream)
+              : launch_sphere_typed<F32>(tokens, pivots, radius_sq, T, d, B, bucket, stream);
+}
 
 namespace {
 

@@ -19,6 +19,10 @@ bool hash_gate_supported(int d, int r, int E, bool bf16);
 hipError_t launch_hash_gate(const void* tokens, const void* rot, const void* gate_w, int64_t T, int d, int L, int r, int E,
                             bool bf16, uint64_t* bucket, float* logits, hipStream_t stream);
 
+// Spherical hash (one bit per sphere, B <= 63 spheres): bucket[t] = B-bit code, bit 0 most significant.
+hipError_t launch_hash_sphere(const void* tokens, const void* pivots, const float* radius_sq, int64_t T, int d, int B,
+                              bool bf16, uint64_t* bucket, hipStream_t stream);
+
 // ---- step 2: group ------------------------------------------------------
 constexpr int kSortTile = 2048;            // assignments per sort tile
 constexpr int kSegTile = 1024;             // sorted positions per cluster-numbering tile

@@ -31,7 +31,7 @@ def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
     assert {"lshmoe_hash", "lshmoe_compress", "lshmoe_decompress", "lshmoe_decompress_combine", "lshmoe_workspace_bytes",
             "lshmoe_backward_workspace_bytes", "lshmoe_decompress_backward", "lshmoe_compress_backward", "lshmoe_hash_gate",
-            "lshmoe_status_string", "lshmoe_last_error", "lshmoe_abi_version", "lshmoe_compress_static", "lshmoe_decompress_combine_backward"} <= set(names)
+            "lshmoe_status_string", "lshmoe_last_error", "lshmoe_abi_version", "lshmoe_compress_static", "lshmoe_decompress_combine_backward", "lshmoe_hash_sphere"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -89,6 +89,10 @@ def test_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.lshmoe_hash(p, p, 16, 60, 2, 8, 1, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED
     assert lib.lshmoe_hash(p, p, 16, 1024, 2, 512, 1, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED   # r > 256
     assert b"256" in lib.lshmoe_last_error()
+    assert lib.lshmoe_hash_sphere(p, p, None, 16, 64, 8, 1, p, None) == lsh.LSHMOE_ERR_NULL
+    assert lib.lshmoe_hash_sphere(p, p, p, 16, 64, 0, 1, p, None) == lsh.LSHMOE_ERR_SHAPE
+    assert lib.lshmoe_hash_sphere(p, p, p, 16, 64, 64, 1, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED   # more than 63 bits
+    assert lib.lshmoe_hash_sphere(p, p, p, 16, 60, 8, 1, p, None) == lsh.LSHMOE_ERR_UNSUPPORTED    # row not whole pieces
     ptrs = [p] * 7
     assert lib.lshmoe_compress(p, p, p, 16, 64, 1, 4, 2, 8, 1, *ptrs, None, 0, None) == lsh.LSHMOE_ERR_WORKSPACE
     assert lib.lshmoe_compress(p, p, p, 16, 64, 1, 4, 2, 8, 1, *ptrs, 0x1010, 1 << 30, None) == lsh.LSHMOE_ERR_WORKSPACE

@@ -421,6 +421,81 @@ def test_hash_gate(H, dtype, T, L, r, E):
         H.WORST[("gate logits", "f32")] = max(H.WORST.get(("gate logits", "f32"), 0.0), float(err.max()))
 
 
+# ------------------------------------------------------------------ spherical hash (Section 4.5, "SP")
+def _check_sphere(H, tokens, pivots, radius_sq, dtype, exact=False):
+    """lshmoe_hash_sphere against the oracle: every bit equal, except that a bit whose squared distance is within
+    1e-4 (relative) of the squared radius may differ (counted).  exact: no bit may differ."""
+    import oracle
+    T, B = tokens.shape[0], pivots.shape[0]
+    xt, pt = H.to_device(tokens, dtype), H.to_device(pivots, dtype)
+    rt = torch.from_numpy(np.ascontiguousarray(radius_sq, dtype=np.float32)).cuda()
+    bt = torch.full((T + 4,), -1, dtype=torch.int64, device="cuda")
+    H.lsh.lshmoe_hash_sphere(xt, pt, rt, bt[:T])
+    torch.cuda.synchronize()
+    assert np.all(bt[T:].cpu().numpy() == -1), "nothing is written past T"
+    got = bt[:T].cpu().numpy().view(np.uint64)
+    ref, bit, margin = oracle.sphere_hash_ref(tokens, pivots, radius_sq.astype(np.float32).astype(np.float64), dtype)
+    assert np.all(got >> np.uint64(B) == 0), "bucket id out of range"
+    gbit = ((got[:, None] >> (np.uint64(B - 1) - np.arange(B, dtype=np.uint64))[None, :]) & np.uint64(1)).astype(np.uint8)
+    diff = gbit != bit
+    bad = diff & (margin >= 1e-4)
+    assert not bad.any(), "spherical hash bit differs away from the surface at (token, sphere) %s" % (np.argwhere(bad)[:8].tolist(),)
+    if exact:
+        assert not diff.any()
+    return got, int(diff.sum())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,d,B", [(1, 64, 1), (300, 72, 5), (4097, 256, 32), (20000, 1024, 33), (65536 + 7, 512, 63),
+                                   (1000, 8, 2), (129, 2048, 17)])
+def test_sphere_hash(H, dtype, T, d, B):
+    rng = np.random.default_rng(900 + T + B)
+    tokens = synth.f32_to_storage(rng.standard_normal((T, d)).astype(np.float32), dtype)
+    pivots = synth.f32_to_storage(rng.standard_normal((B, d)).astype(np.float32), dtype)
+    radius_sq = (2.0 * d + rng.standard_normal(B) * np.sqrt(8.0 * d)).astype(np.float32)    # around the mean squared distance
+    got, flips = _check_sphere(H, tokens, pivots, radius_sq, dtype)
+    gbits = np.unpackbits(got.view(np.uint8).reshape(T, 8), axis=1, bitorder="little")[:, :B]
+    if T >= 300:
+        assert 0.02 < gbits.mean() < 0.98, "balanced radii: both sides of the spheres are populated"
+    print("sphere hash T=%d d=%d B=%d %s: %d borderline bits differ" % (T, d, B, dtype, flips), flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sphere_hash_exact_on_integers(H, dtype):
+    # small integers: every product, sum and squared distance is exact in binary32, and many tokens sit exactly on a
+    # sphere (which counts as inside): no bit may differ
+    rng = np.random.default_rng(77)
+    T, d, B = 5000, 32, 40
+    tokens = synth.f32_to_storage(rng.integers(-4, 5, size=(T, d)).astype(np.float32), dtype)
+    pivots = synth.f32_to_storage(rng.integers(-3, 4, size=(B, d)).astype(np.float32), dtype)
+    radius_sq = rng.integers(250, 420, size=B).astype(np.float32)
+    import oracle
+    _, _, margin = oracle.sphere_hash_ref(tokens, pivots, radius_sq.astype(np.float64), dtype)
+    assert (margin == 0.0).sum() > 100
+    _check_sphere(H, tokens, pivots, radius_sq, dtype, exact=True)
+    # degenerate radii: nothing inside, everything inside
+    got, _ = _check_sphere(H, tokens, pivots, np.full(B, -1.0, np.float32), dtype, exact=True)
+    assert not got.any()
+    got, _ = _check_sphere(H, tokens, pivots, np.full(B, 1e9, np.float32), dtype, exact=True)
+    assert np.all(got == np.uint64((1 << B) - 1))
+
+
+def test_sphere_hash_feeds_the_rest_of_the_path(H):
+    # bucket ids of the spherical hash go through compress and decompress like cross-polytope ones
+    cfg = synth.config("gpt", T=6000, centers=40)
+    w = synth.generate(cfg)
+    B = 11
+    rng = np.random.default_rng(5)
+    pivots = synth.f32_to_storage(rng.standard_normal((B, cfg.d)).astype(np.float32), cfg.dtype)
+    radius_sq = np.full(B, cfg.d * (2.0 + cfg.sigma ** 2), np.float32)
+    got, _ = _check_sphere(H, w.tokens, pivots, radius_sq, cfg.dtype)
+    L, r = (B + 1) // 2, 2                                  # (2r)^L = 4^6 >= 2^11 bounds the ids
+    dummy_rot = np.zeros((L, r, cfg.d), w.rot.dtype)
+    run = H.run_and_check(w.tokens, dummy_rot, w.expert, cfg.E, cfg.dtype, _standin(cfg, w.seed), bucket_override=got,
+                          skip_hash=True)
+    assert run.S < cfg.N                                    # the spheres do put tokens of a mixture centre together
+
+
 def test_path_replays_from_a_graph(H):
     # the calls only enqueue kernels on the caller's stream (no allocation, no host synchronisation, no memset
     # nodes), so a step can be captured once and replayed: three replays on fresh inputs, with eager work and
