@@ -814,12 +814,16 @@ constexpr int kMergeOwn = kBinChunk / kMergeSlices / kBinThreads;  // keys per t
 
 __global__ __launch_bounds__(kBinThreads) void bin_merge_kernel(BinSortArgs a) {
   __shared__ uint64_t other[kBinChunk];  // 16 KB
-  const uint32_t cidx = blockIdx.x / kMergeSlices, slice = blockIdx.x % kMergeSlices;
-  if (a.bin_start[kGroupBins + 2] == 0 || cidx >= a.bin_start[kGroupBins + 1]) return;
+  if (a.bin_start[kGroupBins + 2] == 0) return;   // no bin has several chunks: the usual case
+  // a fixed, small grid walks the (chunk, slice) items: the launch is idle on almost every input, and an idle
+  // launch of one workgroup per item costs 2 us more than this one
+  const uint32_t items = a.bin_start[kGroupBins + 1] * kMergeSlices;
+  for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
+  const uint32_t cidx = item / kMergeSlices, slice = item % kMergeSlices;
   const uint32_t entry = a.chunk_tbl[cidx];
   const uint32_t bin = entry >> 16, chunk = entry & 0xffffu;
   const uint32_t lo_bin = a.bin_start[bin], hi_bin = a.bin_start[bin + 1];
-  if (hi_bin - lo_bin <= (uint32_t)kBinChunk) return;
+  if (hi_bin - lo_bin <= (uint32_t)kBinChunk) continue;   // workgroup-uniform
   const uint32_t chunks = (hi_bin - lo_bin + kBinChunk - 1) / kBinChunk;
   const uint32_t lo = lo_bin + chunk * kBinChunk, hi = min(lo + (uint32_t)kBinChunk, hi_bin);
   const uint32_t n = hi - lo;
@@ -896,6 +900,8 @@ __global__ __launch_bounds__(kBinThreads) void bin_merge_kernel(BinSortArgs a) {
   __syncthreads();
   for (uint32_t t = threadIdx.x; t < tiles; t += kBinThreads)
     if (tile_cnt[t] != 0) atomicAdd(&a.tile_heads[first_tile + t], tile_cnt[t]);
+  __syncthreads();   // `other` is free for the next item
+  }
 }
 
 int bits_for(uint64_t max_value) {  // number of bits needed to hold max_value
@@ -1072,7 +1078,7 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     b.chunk_heads = (uint4*)(ws + plan.off_chunkheads);
     const dim3 chunks((uint32_t)kGroupBins + (N + kBinChunk - 1) / kBinChunk), threads(kBinThreads);
     LSHMOE_LAUNCH(bin_sort_kernel, chunks, threads, kBinSortLds, stream, b);
-    LSHMOE_LAUNCH(bin_merge_kernel, dim3(chunks.x * kMergeSlices), threads, 0, stream, b);
+    LSHMOE_LAUNCH(bin_merge_kernel, dim3(chunks.x * kMergeSlices < 512u ? chunks.x * kMergeSlices : 512u), threads, 0, stream, b);
     // the heads per numbering tile are known: number the clusters (the tile count is within kSelfPrefixMaxTiles here)
     LSHMOE_LAUNCH(seg_write_kernel<true>, dim3(plan.seg_blocks), dim3(kSegThreads), 0, stream,
                        (const uint64_t*)keybuf[1], perm, N, (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert,
