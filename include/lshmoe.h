@@ -68,7 +68,13 @@ typedef enum {
   LSHMOE_ERR_HIP = 5          /* a HIP runtime call failed                          */
 } lshmoe_status;
 
-typedef enum { LSHMOE_F32 = 0, LSHMOE_BF16 = 1 } lshmoe_dtype;
+typedef enum {
+  LSHMOE_F32 = 0,
+  LSHMOE_BF16 = 1,
+  LSHMOE_DTYPE_INT_RANGE_ = 0x7fffffff /* not a dtype: makes every int a representable value, so that an unknown
+                                          code from a caller is an error return (LSHMOE_ERR_UNSUPPORTED), never
+                                          undefined behaviour inside the library */
+} lshmoe_dtype;
 
 /* Flags of lshmoe_decompress. */
 enum {
