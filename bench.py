@@ -360,7 +360,7 @@ def main():
         if len(evg) > 5:
             result["supplementary_hash_gate"] = {
                 "hash_gate_ms": float(np.mean([e0.elapsed_time(e1) for e0, e1 in evg[5:]])), "hash_ms": float(hash_ms),
-                "one_pass_over_tokens": bool(L * r + E <= 128)}
+                "one_pass_over_tokens": bool(L * r + E <= 128 or (L * r <= 256 and E <= 64 and T >= 32768))}
     # context for the hash kernel: the vendor library's GEMM of the same shape (rotation only: [T, d] x [d, L*r],
     # the rotated coordinates written out, no arg-max), timed the same way on the same rotated token copies.
     # It is not part of the path and not part of `value`.

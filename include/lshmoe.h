@@ -162,8 +162,8 @@ lshmoe_status lshmoe_hash_sphere(const void* tokens, const void* pivots, const f
  * paper leaves its form open; routers "via learnable weighting" start from a projection of the token):
  *     logits[t, e] = < gate_w[e, :], tokens[t, :] >,   accumulated in binary32,
  * computed by the same kernel and from the same read of the tokens as the bucket ids whenever
- * L*r + E <= 128 (otherwise the tokens are read a second time for the gate rows).  Choosing the top-k experts
- * from the logits stays with the caller.
+ * L*r + E <= 128, or L*r <= 256 and E <= 64 on at least 32768 tokens (otherwise the tokens are read a second time
+ * for the gate rows).  Choosing the top-k experts from the logits stays with the caller.
  *
  *   gate_w [E, d]  in   dtype
  *   logits [T, E]  out  binary32

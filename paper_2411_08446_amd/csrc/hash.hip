@@ -456,14 +456,19 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
     int row_pieces, int L, int r, int hpg, const char* __restrict__ gate_w = nullptr, int E = 0,
     float* __restrict__ logits = nullptr) {
   using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
-  static_assert(!GATE || HALVES == 1, "the gate rows ride on the unsplit shapes");
-  static_assert(RC == 0 || (!GATE && (RC == 256 ? (MTW == 4 && HALVES == 2) : (RC % 32 == 0 && (MTW * 32) % RC == 0))),
+  // GATE with two halves: each wave's last tile is a tile of gate rows, its first MTW - 1 tiles are rows of R (so
+  // that the hashes split between the halves exactly as without the gate).  Staged rows: HALVES * (MTW - 1) tiles
+  // of R, then HALVES tiles of gate rows.
+  constexpr bool GSPLIT = GATE && HALVES == 2;
+  constexpr int MTH = GSPLIT ? MTW - 1 : MTW;   // tiles of rows of R per wave
+  static_assert(RC == 0 || ((!GATE || GSPLIT) && (RC == 256 ? (MTH == 4 && HALVES == 2) : (RC % 32 == 0 && (MTH * 32) % RC == 0))),
                 "a compile-time r needs whole hashes per wave (or, for r = 256, half a hash)");
   constexpr int WAVES = S::kWaves, TH = WAVES * 64;
   constexpr int LR = S::kRows / 8 / WAVES, LX = S::kTokens / 8 / WAVES;  // direct loads per wave and chunk
   static_assert(S::kRows % (8 * WAVES) == 0 && S::kTokens % (8 * WAVES) == 0, "whole 8-row loads per wave");
-  static_assert(DX == DR + 1 && DR >= 1, "the wait below assumes the tokens run one chunk further ahead than R");
-  constexpr int kAllowed = (DR - 1) * (LR + LX) + LX;  // loads issued after those of chunk c + 1, at the end of iteration c
+  static_assert((DX == DR + 1 || DX == DR) && DR >= 1, "the wait below assumes the tokens run as far ahead as R or one chunk further");
+  // loads issued after those of chunk c + 1, at the end of iteration c (iteration i issues R chunk i + DR, then token chunk i + DX)
+  constexpr int kAllowed = (DR - 1) * (LR + LX) + (DX == DR + 1 ? LX : 0);
   extern __shared__ uint4 lds[];             // R ring [DR + 1][kSlotsR], then token ring [DX + 1][kSlotsX]
   const int tid = threadIdx.x;
   __builtin_assume(tid >= 0 && tid < TH);
@@ -486,7 +491,9 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
   int fslot[kSteps];
 #pragma unroll
   for (int s = 0; s < kSteps; ++s) fslot[s] = n * kPieces + swizzle(n, 2 * s + h);
-  const int a_tile0 = mh * MTW * 32 * kPieces;   // first slot of this wave's row tiles inside an R ring slot
+  const int a_tile0 = mh * MTH * 32 * kPieces;   // first slot of this wave's tiles of R inside an R ring slot
+  // slot of the wave's tile t inside an R ring slot (its gate tile, if any, sits behind all tiles of R)
+  auto a_tile = [&](int t) { return GSPLIT && t == MTH ? (HALVES * MTH + mh) * 32 * kPieces : a_tile0 + t * 32 * kPieces; };
   const int b_tile0 = g * NTW * 32 * kPieces;    // ... and of its token tiles inside a token ring slot
   uint4* const lds_x = lds + (DR + 1) * S::kSlotsR;
 
@@ -500,9 +507,16 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
     const char* arow[LR];                    // this lane's piece of the rows it stages (R first, then the gate rows)
 #pragma unroll
     for (int i = 0; i < LR; ++i) {
-      const int row = min(8 * (wv * LR + i) + sub, rows - 1);
-      arow[i] = (GATE && row >= rows_h ? gate_w + (size_t)(row - rows_h) * row_bytes
-                                       : rot + ((size_t)l0 * r + row) * row_bytes) + pc * 16;
+      const int staged = 8 * (wv * LR + i) + sub;
+      if (GSPLIT) {                          // tiles of R (rows past the last repeat it), then the tiles of gate rows
+        constexpr int kRowsR = HALVES * MTH * 32;
+        arow[i] = (staged >= kRowsR ? gate_w + (size_t)min(staged - kRowsR, E - 1) * row_bytes
+                                    : rot + (size_t)min(staged, rows_h - 1) * row_bytes) + pc * 16;
+      } else {
+        const int row = min(staged, rows - 1);
+        arow[i] = (GATE && row >= rows_h ? gate_w + (size_t)(row - rows_h) * row_bytes
+                                         : rot + ((size_t)l0 * r + row) * row_bytes) + pc * 16;
+      }
     }
 
     auto stage_r = [&](int chunk) {
@@ -541,14 +555,14 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
       const uint4* bufb = lds_x + (c % (DX + 1)) * S::kSlotsX;
       uint4 fa[2][MTW], fb[2][NTW];          // fragments of the step in flight and of the next one
 #pragma unroll
-      for (int t = 0; t < MTW; ++t) fa[0][t] = bufa[a_tile0 + t * 32 * kPieces + fslot[0]];
+      for (int t = 0; t < MTW; ++t) fa[0][t] = bufa[a_tile(t) + fslot[0]];
 #pragma unroll
       for (int u = 0; u < NTW; ++u) fb[0][u] = bufb[b_tile0 + u * 32 * kPieces + fslot[0]];
 #pragma unroll
       for (int s = 0; s < kSteps; ++s) {
         if (s + 1 < kSteps) {
 #pragma unroll
-          for (int t = 0; t < MTW; ++t) fa[(s + 1) & 1][t] = bufa[a_tile0 + t * 32 * kPieces + fslot[s + 1]];
+          for (int t = 0; t < MTW; ++t) fa[(s + 1) & 1][t] = bufa[a_tile(t) + fslot[s + 1]];
 #pragma unroll
           for (int u = 0; u < NTW; ++u) fb[(s + 1) & 1][u] = bufb[b_tile0 + u * 32 * kPieces + fslot[s + 1]];
         }
@@ -567,8 +581,8 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
     uint2* ex = reinterpret_cast<uint2*>(lds);   // [HALVES][kTokens][nh]: {magnitude bits, row | sign << 31}
     if constexpr (RC != 0) {
       // r is the constant RC: this wave's MTW tiles are kSeg whole hashes (for r = 256, half of the one hash)
-      constexpr int kSegTiles = RC / 32 < MTW ? RC / 32 : MTW;   // tiles per hash inside this wave
-      constexpr int kSeg = MTW / kSegTiles;                      // hashes (or hash parts) per wave
+      constexpr int kSegTiles = RC / 32 < MTH ? RC / 32 : MTH;   // tiles per hash inside this wave
+      constexpr int kSeg = MTH / kSegTiles;                      // hashes (or hash parts) per wave
       const int mhu = __builtin_amdgcn_readfirstlane(mh);
       static_for<kSeg>([&](auto sc) {
         constexpr int sg = decltype(sc)::value;
@@ -601,8 +615,8 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
         int pmax = (int)0x80000000;
         uint32_t nmax = 0;
 #pragma unroll
-        for (int t = 0; t < MTW; ++t) {
-          const int row0 = (mh * MTW + t) * 32;
+        for (int t = 0; t < MTH; ++t) {
+          const int row0 = (mh * MTH + t) * 32;
           if (row0 + 31 < lo || row0 >= lo + r) continue;  // wave-uniform
 #pragma unroll
           for (int jb = 0; jb < 4; ++jb) {
@@ -624,8 +638,8 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
         int bi = 0x7fffffff;
         uint32_t wbits = neg ? 0x80000000u : 0u;           // pattern of the value at the lowest row of largest magnitude
 #pragma unroll
-        for (int t = MTW - 1; t >= 0; --t) {
-          const int row0 = (mh * MTW + t) * 32;
+        for (int t = MTH - 1; t >= 0; --t) {
+          const int row0 = (mh * MTH + t) * 32;
           if (row0 + 31 < lo || row0 >= lo + r) continue;
 #pragma unroll
           for (int jb = 3; jb >= 0; --jb) {
@@ -666,10 +680,12 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
       for (int u = 0; u < NTW; ++u) {
         const uint32_t tok = tok_blk + (uint32_t)(g * NTW * 32 + u * 32 + n);
 #pragma unroll
-        for (int t = 0; t < MTW; ++t) {
+        for (int t = GSPLIT ? MTH : 0; t < MTW; ++t) {
 #pragma unroll
           for (int jb = 0; jb < 4; ++jb) {
-            const int e0 = t * 32 + 8 * jb + 4 * h - rows_h;   // rows_h is a multiple of 8: e0 is a multiple of 4
+            // rows_h is a multiple of 8: e0 is a multiple of 4.  With two halves the wave's gate tile holds gate rows
+            // 32 mh .. 32 mh + 31.
+            const int e0 = GSPLIT ? mh * 32 + 8 * jb + 4 * h : t * 32 + 8 * jb + 4 * h - rows_h;
             if (tok >= T || e0 < 0 || e0 >= E) continue;
             float* dst = logits + (size_t)tok * E + e0;
             if (e0 + 3 < E && (E & 3) == 0) {
@@ -694,7 +710,7 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
             uint32_t code;
             if constexpr (RC != 0 && RC != 256) {
               // whole hashes per wave: hash lh was finished by the wave of half lh / (hashes per wave)
-              constexpr int kPerWave = MTW * 32 / RC;
+              constexpr int kPerWave = MTH * 32 / RC;
               code = ex[((lh / kPerWave) * S::kTokens + tok) * nh + lh].y;
             } else {
               const uint2 lo_half = ex[tok * nh + lh], hi_half = ex[(S::kTokens + tok) * nh + lh];
@@ -724,6 +740,7 @@ hipError_t launch_stream(const char* x, const char* R, uint64_t* bucket, int64_t
   using S = StreamShape<MTW, NTW, GROUPS, HALVES, DR, DX>;
   static_assert(S::kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
   if ((GATE ? L * r + E : hpg * r) > S::kRows) return hipErrorInvalidValue;  // the instance must hold every row of a pass
+  if (GATE && HALVES == 2 && (L * r > HALVES * (MTW - 1) * 32 || E > HALVES * 32 || L < 1)) return hipErrorInvalidValue;
   if (RC != 0 && r != RC) return hipErrorInvalidValue;                       // a compile-time r must be the real one
   auto kern = hash_stream_kernel<DT, MTW, NTW, GROUPS, HALVES, DR, DX, GATE, RC>;
   static std::atomic<bool> raised{false};  // set once per kernel; repeating the call is harmless
@@ -795,9 +812,14 @@ hipError_t launch_typed(const void* tokens, const void* rot, int64_t T, int d, i
   // else 64-token workgroups of two waves three chunks ahead.
   if (fast && mt <= 4 && T >= 8192) {
     const bool big = T >= 24576;
+    // beyond 256 workgroups of 128 tokens (one per compute unit): shorter rings (at most 80 KB), so that two
+    // workgroups share a compute unit's LDS and the workgroups past the first 256 do not wait for a second round
+    // (measured at T = 65536, d = 1024: 64 rows 29.8 -> 26.8 us, 128 rows 34.1 -> 29.3 us; T = 131072, 128 rows 65.8 -> 54.5 us)
+    const bool huge = T > 256 * 128;
 #define LSHMOE_STREAM(MT, RC) \
-    (big ? launch_stream<DT, MT, 1, 4, 1, 3, 4, false, RC>(x, R, bucket, T, row_pieces, L, r, hpg, stream) \
-         : launch_stream<DT, MT, 1, 2, 1, 2, 3, false, RC>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
+    (huge ? launch_stream<DT, MT, 1, 4, 1, 1, 2, false, RC>(x, R, bucket, T, row_pieces, L, r, hpg, stream) \
+     : big ? launch_stream<DT, MT, 1, 4, 1, 3, 4, false, RC>(x, R, bucket, T, row_pieces, L, r, hpg, stream) \
+           : launch_stream<DT, MT, 1, 2, 1, 2, 3, false, RC>(x, R, bucket, T, row_pieces, L, r, hpg, stream))
     // r = 32 and r = 64 (whole hashes per tile or per two tiles) take the arg-max with compile-time row ranges
     if (mt <= 1) return r == 32 ? LSHMOE_STREAM(1, 32) : LSHMOE_STREAM(1, 0);
     if (mt == 2) return r == 32 ? LSHMOE_STREAM(2, 32) : r == 64 ? LSHMOE_STREAM(2, 64) : LSHMOE_STREAM(2, 0);
@@ -857,9 +879,11 @@ hipError_t launch_gate_rows(const char* x, const char* R, const char* W, int64_t
                             uint64_t* bucket, float* logits, hipStream_t stream) {
   const int mt = (L * r + E + 31) / 32;
   const bool big = T >= 24576;
+  const bool huge = T > 256 * 128;   // as for the hash alone: two workgroups per compute unit
 #define LSHMOE_GATE(MT)                                                                                               \
-  (big ? launch_stream<DT, MT, 1, 4, 1, 3, 4, true>(x, R, bucket, T, row_pieces, L, r, L > 0 ? L : 1, stream, W, E, logits) \
-       : launch_stream<DT, MT, 1, 2, 1, 2, 3, true>(x, R, bucket, T, row_pieces, L, r, L > 0 ? L : 1, stream, W, E, logits))
+  (huge ? launch_stream<DT, MT, 1, 4, 1, 1, 2, true>(x, R, bucket, T, row_pieces, L, r, L > 0 ? L : 1, stream, W, E, logits) \
+   : big ? launch_stream<DT, MT, 1, 4, 1, 3, 4, true>(x, R, bucket, T, row_pieces, L, r, L > 0 ? L : 1, stream, W, E, logits) \
+         : launch_stream<DT, MT, 1, 2, 1, 2, 3, true>(x, R, bucket, T, row_pieces, L, r, L > 0 ? L : 1, stream, W, E, logits))
   if (mt <= 1) return LSHMOE_GATE(1);
   if (mt == 2) return LSHMOE_GATE(2);
   if (mt == 3) return LSHMOE_GATE(3);
@@ -876,6 +900,15 @@ hipError_t launch_hash_gate_typed(const void* tokens, const void* rot, const voi
   auto W = (const char*)gate_w;
   if ((int64_t)L * r + E <= 128)  // one pass over the tokens for both
     return launch_gate_rows<DT>(x, R, W, T, row_pieces, L, r, E, bucket, logits, stream);
+  // Up to 256 rows of R and 64 gate rows on large inputs: still one pass, on the shape of the widest hash instance
+  // with a fifth tile per wave for the gate rows.  All of LDS goes to two ring slots per operand, so the tokens run
+  // only one chunk ahead; that is slower per chunk than the hash alone but far cheaper than a second pass over the
+  // tokens (measured at T = 65536, d = 1024, 256 + 64 rows: see the benchmark's supplementary_hash_gate).
+  if ((int64_t)L * r <= 256 && E <= 64 && T >= 32768) {
+#define LSHMOE_GATE_WIDE(RC) launch_stream<DT, 5, 2, 4, 2, 1, 1, true, RC>(x, R, bucket, T, row_pieces, L, r, L, stream, W, E, logits)
+    return r == 64 ? LSHMOE_GATE_WIDE(64) : r == 32 ? LSHMOE_GATE_WIDE(32) : r == 128 ? LSHMOE_GATE_WIDE(128) : LSHMOE_GATE_WIDE(0);
+#undef LSHMOE_GATE_WIDE
+  }
   // too many rows for one accumulator set: the hash as usual, then the gate rows alone (the tokens are read twice)
   hipError_t e = launch_typed<DT>(tokens, rot, T, d, L, r, bucket, stream);
   if (e != hipSuccess) return e;

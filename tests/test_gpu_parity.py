@@ -250,7 +250,9 @@ def test_exact_ties_on_the_fast_hash_instance(H, dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("T,L,r", [(65536 + 77, 4, 64), (65536 + 77, 2, 256), (65536 + 77, 7, 32),
                                    (65536 + 77, 5, 32), (65536 + 77, 6, 32),
-                                   (32768 + 77, 3, 32), (24576 + 3, 1, 16), (16384 + 5, 2, 32), (8192 + 1, 2, 64)])
+                                   (32768 + 77, 3, 32), (24576 + 3, 1, 16), (16384 + 5, 2, 32), (8192 + 1, 2, 64),
+                                   # beyond 256 workgroups of 128 tokens: the short-ring instances, 1..4 row tiles
+                                   (65536 + 77, 1, 16), (40000, 2, 64), (50000 + 1, 4, 32), (33000, 2, 32), (70000, 3, 40)])
 def test_hash_streaming_instances(H, dtype, T, L, r):
     _hash_case(H, dtype, T, L, r)
 
@@ -384,7 +386,13 @@ def test_backward_long_clusters(H, dtype):
                                      (100, 2, 16, 128),         # tiny T, widest gate
                                      (5000, 12, 8, 30),         # 96 + 30 rows
                                      (20000, 6, 16, 1),         # a single gate row: a logit can cancel to almost nothing
-                                     (24576, 10, 32, 2)])       # 320 hash rows (two passes), two gate rows
+                                     (24576, 10, 32, 2),        # 320 hash rows (two passes), two gate rows
+                                     (40000, 8, 32, 64),        # 256 + 64 rows in one pass: a gate tile per wave half, r = 32
+                                     (33000, 2, 128, 40),       # ... r = 128, the second gate tile partly filled
+                                     (50001, 5, 40, 7),         # ... hashes that straddle tiles and halves (generic arg-max), odd E
+                                     (65536, 1, 256, 64),       # ... one hash over both halves
+                                     (32768, 3, 64, 33),        # ... three of four hashes, one row in the second gate tile
+                                     (40000 + 5, 2, 32, 16)])   # more than 256 workgroups: the short-ring gate instance
 def test_hash_gate(H, dtype, T, L, r, E):
     import oracle
     d = 256 if dtype == "bf16" else 128
