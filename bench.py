@@ -467,7 +467,9 @@ def main():
     torch.cuda.synchronize()
     if len(evc) > 5:
         cb_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evc[5:]]))
-        cb_bytes = (S + 2 * T + n_multi_assign + n_multi_seg + N) * row + 12 * N + 4 * (S + 1)
+        # expert-output rows once per cluster, token and centroid rows where the residual can be non-zero, the output
+        # gradient once per token, one row gradient written per assignment
+        cb_bytes = (S + n_multi_assign + n_multi_seg + T + N) * row + 12 * N + 4 * (S + 1)
         result["supplementary_combine_backward"] = {"ms": cb_ms, "algorithmic_bytes": cb_bytes,
                                                     "achieved_gbs": cb_bytes / (cb_ms * 1e-3) / 1e9}
     del go, gwo, gyo
