@@ -13,12 +13,12 @@
 //    histogram kernel writes the tile's digit counts as one row of a tile-major
 //    table and every scatter block derives its own output offsets from that
 //    small table, so there is no scan launch), then one launch that sorts every
-//    bin on the remaining bits inside LDS (in chunks of 2048 keys), one launch
-//    that merges the chunks of bins that have several (it leaves at once when
-//    there are none), and one launch that numbers the clusters from the head
-//    counts the two bin kernels left per tile: five launches whatever the key
-//    width.  (Before: a histogram and a scatter launch per 9 key bits, and a
-//    counting launch.)
+//    bin on the remaining bits inside LDS (in chunks of 2048 keys; the chunks of
+//    a bin that has several are merged in the same launch by the workgroups
+//    that sorted them, the later of two neighbours each time), and one launch
+//    that numbers the clusters from the head counts the bin kernel left per
+//    tile: four launches whatever the key width.  (Before: a histogram and a
+//    scatter launch per 9 key bits, and a counting launch.)
 //  - larger: least-significant-digit radix passes of histogram,
 //    single-workgroup scan of the (bin, tile) table and scatter.
 //
@@ -182,11 +182,7 @@ __device__ __forceinline__ void write_chunk_table(uint32_t total0, uint32_t tota
   const uint32_t at1 = half + block_exclusive_scan(c1, wave_sum, rest);
   for (uint32_t j = 0; j < c0; ++j) chunk_tbl[at0 + j] = (threadIdx.x << 16) | j;
   for (uint32_t j = 0; j < c1; ++j) chunk_tbl[at1 + j] = ((threadIdx.x + 256u) << 16) | j;
-  const int several = __syncthreads_or(c0 > 1 || c1 > 1);
-  if (threadIdx.x == 0) {
-    bin_start[kGroupBins + 1] = half + rest;
-    bin_start[kGroupBins + 2] = several ? 1u : 0u;
-  }
+  if (threadIdx.x == 0) bin_start[kGroupBins + 1] = half + rest;
 }
 
 struct PassArgs {
@@ -195,7 +191,7 @@ struct PassArgs {
   uint32_t nblk;
   const uint32_t* table;  // FUSED: tile-major counts of this pass; else the scanned bin-major offsets
   uint32_t* bin_start;    // FUSED, optional: block 0 writes the first output position of every bin, then N,
-  uint32_t* chunk_tbl;    // then the number of chunks and whether a bin has several; and the chunk table
+  uint32_t* chunk_tbl;    // then the number of chunks; and the chunk table
 };
 
 template <bool FIRST, bool FUSED, int TILE = kSortTile>
@@ -595,8 +591,8 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_group_kernel(KeySource
 // Most-significant-digit route (up to kFusedMaxTiles tiles): ONE global pass on the top digit of the key
 // splits the assignments into up to 512 bins (stable, so a bin keeps ascending assignment order).  A bin
 // is cut into chunks of at most kBinChunk consecutive keys; one workgroup sorts one chunk on the remaining
-// key bits inside LDS; a bin of several chunks is then merged by rank.  That replaces a histogram and a
-// scatter launch per further digit by one launch (two when some bin has more than kBinChunk keys).
+// key bits inside LDS; the chunks of a bin of several are then merged pairwise, in the same launch (merge_up).
+// That replaces a histogram and a scatter launch per further digit by one launch.
 //
 // Chunk sort, two ways:
 //   up to kBinFast keys and no crowded sub-bin: the keys are thrown into sub-bins by their next (up to) 8
@@ -607,10 +603,10 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_group_kernel(KeySource
 //     chunk; counts per (wave, digit); ranks inside a round of 64 keys from wave ballots), the last pass
 //     writing to global memory.  Its cost does not depend on how many keys are equal.
 struct BinSortArgs {
-  const uint32_t* bin_start;  // [bins + 1], then [bins + 1] = number of chunks, [bins + 2] = 1 if a bin has several
+  const uint32_t* bin_start;  // [bins + 1], then [bins + 1] = number of chunks
   const uint32_t* chunk_tbl;  // chunk w is chunk (entry & 0xffff) of bin (entry >> 16)
   uint64_t* key[2];           // [0]: keys after the global pass; [1]: receives the sorted keys
-  int32_t* idx[2];            // [0]: assignment ids after the global pass
+  int32_t* idx[2];            // [0]: assignment ids after the global pass; [1]: second buffer of the chunk merges
   int32_t* perm;              // receives the sorted assignment ids
   int passes;                 // radix passes over the low key bits
   int shift[8], width[8];     // their digits, least significant first
@@ -618,6 +614,8 @@ struct BinSortArgs {
   uint32_t sub_mask;
   uint32_t* tile_heads;       // [tiles of kSegTile positions]: cluster heads per tile of bins of several chunks (atomics)
   uint4* chunk_heads;         // [chunks]: {first tile, heads in it, in the next, in the one after} of a bin of one chunk
+  uint32_t* merge_arrivals;   // [chunks], zero on entry: runs that have arrived at a merge, indexed by the chunk that
+                              // starts the merge's right-hand run
 };
 
 // Publishes the heads counted in LDS per numbering tile (a chunk's positions touch at most kChunkTiles of them)
@@ -638,6 +636,211 @@ constexpr int kSubBins = 256;
 constexpr uint32_t kSubBinCrowd = 32;              // a sub-bin with more keys sends the chunk the radix way
 constexpr size_t kBinSortLds = 2 * (size_t)kBinChunk * (8 + 4);  // two (key, id) buffers: 48 KB
 
+// Merge of the sorted chunks of a bin that has several, inside the launch that sorts the chunks.  The chunks of
+// the bin are the leaves of a binary tree: the node of level j that covers chunks [i 2^j, (i + 1) 2^j) merges the
+// sorted runs of its two children.  Nobody waits: a workgroup that has finished a run adds one to the node's
+// arrival counter; the first to arrive leaves, the second finds both runs complete (fence, device-scope atomic,
+// fence), merges them and carries the result one level up.  A run without a right-hand neighbour is copied, so
+// that every run of a level sits in the same one of the two buffers and a merge never writes where it reads; the
+// chunk sort starts in the buffer from which the root's output lands in the final arrays.  The merge is stable
+// (on equal keys the left run, i.e. the lower assignment ids, goes first) and proceeds in tiles of kBinChunk
+// outputs: the tile's share of either run is found by bisection along the merge path (all boundaries at once, one
+// per thread), staged in LDS, ranked there by bisection, and written out in order.  The root also counts the
+// cluster heads per numbering tile.  Depth is log2 of the bin's chunk count, so one bin that holds the whole input
+// still takes about as long as the separate merge launch this replaces, which was idle on almost every input.
+struct MergeLds {
+  uint64_t in_key[kBinChunk];    // the tile's share of the left run, then of the right run
+  uint64_t out_key[kBinChunk];
+  int32_t in_idx[kBinChunk];
+  int32_t out_idx[kBinChunk];
+};
+static_assert(sizeof(MergeLds) == 2 * (size_t)kBinChunk * (8 + 4), "the merge reuses the chunk sort's dynamic LDS");
+struct MergeState {                    // small LDS state of a merge, double buffered by tile parity
+  uint32_t tile_cnt[2][kChunkTiles];   // heads of a tile's outputs per numbering tile
+  uint64_t last_key[2];                // a tile's last output
+  uint32_t flag;                       // what the arrival counter held
+};
+
+// Number of elements of the left run among the first `diag` outputs of the stable merge of A[0, na) and B[0, nb):
+// the first x in [lo, hi] for which "A[x] goes before B[diag - 1 - x]" no longer holds.  Sixteen probes per step
+// instead of one: the runs were written by other compute units and every probe is a trip to memory, so the
+// number of dependent steps is what counts (4 for 65536 keys instead of 16).
+__device__ __forceinline__ uint32_t merge_path_split(const uint64_t* A, uint32_t na, const uint64_t* B, uint32_t nb,
+                                                     uint32_t diag) {
+  constexpr int kProbes = 16;
+  uint32_t lo = diag > nb ? diag - nb : 0u, hi = min(diag, na);
+  while (lo < hi) {
+    const uint32_t w = (hi - lo + kProbes - 1) / kProbes;   // >= 1
+    uint64_t av[kProbes], bv[kProbes];
+#pragma unroll
+    for (int i = 0; i < kProbes; ++i) {                      // probe i sits at lo + i w; past hi it re-reads the last valid one
+      const uint32_t x = min(lo + (uint32_t)i * w, hi - 1);  // lo <= x < hi <= min(diag, na); diag - 1 - x in [0, nb)
+      av[i] = A[x];
+      bv[i] = B[diag - 1 - x];
+    }
+    uint32_t before = 0;                                     // probes whose A element goes first: a prefix of them
+#pragma unroll
+    for (int i = 0; i < kProbes; ++i) before += (lo + (uint32_t)i * w < hi && av[i] <= bv[i]) ? 1u : 0u;
+    if (before == 0) return lo;
+    const uint32_t next = lo + before * w;                   // the first probe that failed, if there is one below hi
+    lo = lo + (before - 1) * w + 1;
+    hi = before < (uint32_t)kProbes && next < hi ? next : hi;
+  }
+  return lo;
+}
+
+// Slot of element i of a staged tile.  The bisection below probes indices that differ by multiples of a power of
+// two; stored plainly those all fall into the same LDS bank (up to 64 lanes one after the other, which made the
+// ranking 8 us per tile); swapping the low five index bits around by the next ten spreads them.
+__device__ __forceinline__ uint32_t merge_slot(uint32_t i) { return i ^ ((i >> 5) & 31u) ^ ((i >> 10) & 31u); }
+static_assert(kBinChunk <= (1 << 15), "merge_slot permutes indices below 2^15 inside blocks of 32");
+
+// Barrier that orders LDS accesses only: unlike __syncthreads() it does not wait for the wave's global loads and
+// stores, which inside the merge loop are a prefetch that should stay in flight and outputs nobody in the workgroup
+// reads before the merge ends.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Every thread of the workgroup calls it (kBinThreads threads).  src/dst: the two buffers; the runs are
+// src[lo_a, lo_a + na) and src[lo_a + na, lo_a + na + nb); the output is dst[lo_a, lo_a + na + nb).
+// count_heads: also adds the heads of the output to tile_heads (the output is final).
+// (No __restrict__ on the runs: other workgroups wrote them during this launch, and every load of them has to stay
+// an ordinary vector load behind the fence.)
+__device__ __forceinline__ void merge_runs(const uint64_t* src_key, const int32_t* src_idx, uint64_t* dst_key, int32_t* dst_idx,
+                           uint32_t lo_a, uint32_t na, uint32_t nb, bool count_heads, uint32_t* tile_heads, MergeLds& m,
+                           uint32_t* split /*[kFusedMaxTiles + 1] in LDS*/, MergeState& st) {
+  constexpr int kItems = kBinChunk / kBinThreads;   // elements of a tile per thread: 8
+  const uint64_t* A = src_key + lo_a;
+  const uint64_t* B = A + na;
+  const uint32_t n = na + nb, tiles = (n + kBinChunk - 1) / kBinChunk;   // tiles <= kFusedMaxTiles
+  __syncthreads();   // LDS of an earlier merge (or of the chunk sort) is no longer read
+  for (uint32_t t = threadIdx.x; t <= tiles; t += kBinThreads)
+    split[t] = t == 0 ? 0u : t == tiles ? na : merge_path_split(A, na, B, nb, t * kBinChunk);
+  __syncthreads();
+  // a tile's inputs are fetched into registers one tile ahead, so that the loads fly while the tile before is ranked
+  uint64_t pk[kItems];
+  int32_t pi[kItems];
+  auto fetch = [&](uint32_t t) {
+    const uint32_t a0 = split[t], a1 = split[t + 1];
+    const uint32_t out0 = t * kBinChunk, out1 = min(out0 + (uint32_t)kBinChunk, n);
+    const uint32_t b0 = out0 - a0, ca = a1 - a0, cn = out1 - out0;
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+      const uint32_t e = threadIdx.x + q * kBinThreads;
+      const uint32_t from = min(e < ca ? lo_a + a0 + e : lo_a + na + b0 + (e - ca), lo_a + n - 1);  // e >= cn: unused
+      pk[q] = src_key[from];
+      pi[q] = src_idx[from];
+      (void)cn;
+    }
+  };
+  fetch(0);
+  for (uint32_t t = 0; t < tiles; ++t) {
+    const uint32_t a0 = split[t], a1 = split[t + 1];
+    const uint32_t out0 = t * kBinChunk, out1 = min(out0 + (uint32_t)kBinChunk, n);
+    const uint32_t ca = a1 - a0, cn = out1 - out0, cb = cn - ca;   // cn <= kBinChunk
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+      const uint32_t e = threadIdx.x + q * kBinThreads;
+      if (e < cn) {
+        m.in_key[merge_slot(e)] = pk[q];
+        m.in_idx[e] = pi[q];
+      }
+    }
+    if (count_heads && threadIdx.x < (uint32_t)kChunkTiles) st.tile_cnt[t & 1][threadIdx.x] = 0;
+    lds_barrier();
+    if (t + 1 < tiles) fetch(t + 1);
+    if (count_heads && t > 0 && threadIdx.x < (uint32_t)kChunkTiles && st.tile_cnt[(t - 1) & 1][threadIdx.x] != 0)
+      atomicAdd(&tile_heads[((lo_a + out0 - kBinChunk) >> kSegTileBits) + threadIdx.x], st.tile_cnt[(t - 1) & 1][threadIdx.x]);
+    {
+      // Every thread produces kItems consecutive outputs of the tile: one bisection along the merge path finds how
+      // many of the outputs before its first one come from the left part, then it merges step by step (on equal
+      // keys the left part goes first).  A wave runs alone on its SIMD here, so instructions per key are what
+      // counts: ranking every key by a bisection of its own took eight times as many.
+      const uint32_t diag = min(threadIdx.x * (uint32_t)kItems, cn);
+      uint32_t lo = diag > cb ? diag - cb : 0u, hi = min(diag, ca);
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;   // mid < ca; diag - 1 - mid in [0, cb)
+        if (m.in_key[merge_slot(mid)] <= m.in_key[merge_slot(ca + diag - 1 - mid)]) lo = mid + 1; else hi = mid;
+      }
+      uint32_t ai = lo, bi = ca + (diag - lo);   // next element of either part, as indices into in_key
+      const uint32_t last = kBinChunk - 1;     // reads past a part's end are clamped and never chosen
+      uint64_t ka = m.in_key[merge_slot(min(ai, last))], kb = m.in_key[merge_slot(min(bi, last))];
+#pragma unroll
+      for (int q = 0; q < kItems; ++q) {
+        const uint32_t at = diag + q;
+        const bool take_a = ai < ca && (bi >= cn || ka <= kb);
+        if (at < cn) {
+          m.out_key[at] = take_a ? ka : kb;
+          m.out_idx[at] = m.in_idx[take_a ? ai : bi];
+        }
+        if (take_a) { ++ai; ka = m.in_key[merge_slot(min(ai, last))]; }
+        else { ++bi; kb = m.in_key[merge_slot(min(bi, last))]; }
+      }
+    }
+    lds_barrier();
+    const uint32_t first_tile = (lo_a + out0) >> kSegTileBits;
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+      const uint32_t e = threadIdx.x + q * kBinThreads;
+      if (e < cn) {
+        const uint64_t key = m.out_key[e];
+        dst_key[lo_a + out0 + e] = key;
+        dst_idx[lo_a + out0 + e] = m.out_idx[e];
+        if (e == cn - 1) st.last_key[t & 1] = key;   // the key before the next tile's first output
+        if (count_heads) {
+          // the first key of a bin always starts a cluster: the key before it belongs to another bin
+          const bool head = e == 0 ? (t == 0 || st.last_key[(t - 1) & 1] != key) : m.out_key[e - 1] != key;
+          if (head) atomicAdd(&st.tile_cnt[t & 1][((lo_a + out0 + e) >> kSegTileBits) - first_tile], 1u);
+        }
+      }
+    }
+    // the next tile's staging writes touch in_*, which nobody reads any more; out_* is read until the barrier that
+    // follows those writes, and written again only after it
+  }
+  __syncthreads();
+  if (count_heads && threadIdx.x < (uint32_t)kChunkTiles && st.tile_cnt[(tiles - 1) & 1][threadIdx.x] != 0)
+    atomicAdd(&tile_heads[((lo_a + (tiles - 1) * kBinChunk) >> kSegTileBits) + threadIdx.x], st.tile_cnt[(tiles - 1) & 1][threadIdx.x]);
+}
+
+// Called by every thread of a workgroup that has just written chunk `chunk` of a bin of several chunks, sorted,
+// into buffer `start_buf`.  Returns when the workgroup has nothing left to merge.
+__device__ __forceinline__ void merge_up(const BinSortArgs& a, uint32_t lo_bin, uint32_t hi_bin, uint32_t chunk, uint32_t first_chunk_slot,
+                         MergeLds& m, uint32_t* split, MergeState& st) {
+  const uint32_t chunks = (hi_bin - lo_bin + kBinChunk - 1) / kBinChunk;
+  int levels = 0;
+  while ((1u << levels) < chunks) ++levels;
+  uint32_t buf = (levels & 1) ? 0u : 1u;          // where the sorted chunks are: the root's output lands in buffer 1
+  for (int j = 1; j <= levels; ++j, buf ^= 1u) {
+    const uint32_t left0 = (chunk >> j) << j, right0 = left0 + (1u << (j - 1));
+    const uint32_t lo_a = lo_bin + left0 * kBinChunk;
+    const bool final_level = j == levels;
+    const uint64_t* src_key = buf ? a.key[1] : a.key[0];
+    const int32_t* src_idx = buf ? a.idx[1] : a.idx[0];
+    uint64_t* dst_key = buf ? a.key[0] : a.key[1];
+    int32_t* dst_idx = final_level ? a.perm : buf ? a.idx[0] : a.idx[1];   // the root writes buffer 1's keys and the result ids
+    if (right0 >= chunks) {
+      // no right-hand run (never at the root): move the run to the buffer its level's outputs live in
+      const uint32_t n = hi_bin - lo_a;
+      for (uint32_t e = threadIdx.x; e < n; e += kBinThreads) {
+        dst_key[lo_a + e] = src_key[lo_a + e];
+        dst_idx[lo_a + e] = src_idx[lo_a + e];
+      }
+      __syncthreads();   // the next level may copy again, reading what other threads wrote here
+      continue;
+    }
+    __threadfence();      // this workgroup's run is visible device-wide before the counter moves
+    __syncthreads();
+    if (threadIdx.x == 0) st.flag = atomicAdd(&a.merge_arrivals[first_chunk_slot + right0], 1u);
+    __syncthreads();
+    if (st.flag == 0u) return;   // the other run is still being made: its workgroup will find this one complete
+    __threadfence();      // second to arrive: the other run is complete and visible
+    const uint32_t na = (right0 - left0) * kBinChunk;             // a left-hand run is always full
+    const uint32_t end = min(lo_bin + (left0 + (1u << j)) * kBinChunk, hi_bin);
+    merge_runs(src_key, src_idx, dst_key, dst_idx, lo_a, na, end - lo_a - na, final_level, a.tile_heads, m, split, st);
+  }
+}
+
 __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
   extern __shared__ uint64_t bin_lds[];            // radix way: keys [2][kBinChunk], then ids [2][kBinChunk]
   __shared__ uint32_t cnt[kBinWaves][kGroupBins];  // 8 KB; the sub-bin way keeps its keys here
@@ -645,6 +848,8 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
   __shared__ uint32_t sub_cnt[kSubBins], sub_base[kSubBins];
   __shared__ uint32_t wave_sum[kBinWaves];
   __shared__ uint32_t tile_cnt[kChunkTiles];
+  __shared__ MergeState merge_state;
+  static_assert(sizeof(cnt) >= (kFusedMaxTiles + 1) * sizeof(uint32_t), "the merge keeps its tile boundaries in cnt");
   if (blockIdx.x >= a.bin_start[kGroupBins + 1]) return;
   if (threadIdx.x < (uint32_t)kChunkTiles) tile_cnt[threadIdx.x] = 0;  // a barrier follows on every way
   const uint32_t entry = a.chunk_tbl[blockIdx.x];
@@ -652,10 +857,19 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
   const uint32_t lo_bin = a.bin_start[bin], hi_bin = a.bin_start[bin + 1];
   const uint32_t lo = lo_bin + chunk * kBinChunk, hi = min(lo + (uint32_t)kBinChunk, hi_bin);
   const uint32_t n = hi - lo;
-  // a bin of one chunk is finished here; the chunks of a larger bin are sorted in place and merged afterwards
+  // a bin of one chunk is finished here; the chunks of a larger bin are merged by the workgroups that sorted
+  // them (merge_up), starting from the buffer that makes the last merge land in the final arrays
   const bool alone = hi_bin - lo_bin <= (uint32_t)kBinChunk;
-  uint64_t* out_key = alone ? a.key[1] : a.key[0];
-  int32_t* out_idx = alone ? a.perm : a.idx[0];
+  uint32_t start_buf = 0;
+  if (!alone) {
+    const uint32_t chunks = (hi_bin - lo_bin + kBinChunk - 1) / kBinChunk;
+    int levels = 0;
+    while ((1u << levels) < chunks) ++levels;
+    start_buf = (levels & 1) ? 0u : 1u;
+  }
+  uint64_t* out_key = alone || start_buf ? a.key[1] : a.key[0];
+  int32_t* out_idx = alone ? a.perm : start_buf ? a.idx[1] : a.idx[0];
+  MergeLds& merge_lds = *reinterpret_cast<MergeLds*>(bin_lds);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   if (n <= (uint32_t)kBinFast) {
@@ -721,6 +935,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
         }
       }
       publish_chunk_heads(tile_cnt, lo >> kSegTileBits, a.chunk_heads + blockIdx.x);  // zeros unless alone
+      if (!alone) merge_up(a, lo_bin, hi_bin, chunk, blockIdx.x - chunk, merge_lds, &cnt[0][0], merge_state);
       return;
     }
     __syncthreads();  // the radix way below reuses cnt
@@ -801,107 +1016,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_sort_kernel(BinSortArgs a) {
     if (alone && (i == 0 || fkey[i - 1] != k)) atomicAdd(&tile_cnt[((lo + i) >> kSegTileBits) - (lo >> kSegTileBits)], 1u);
   }
   publish_chunk_heads(tile_cnt, lo >> kSegTileBits, a.chunk_heads + blockIdx.x);  // zeros unless alone
-}
-
-// Merge of the sorted chunks of a bin that has several: the final place of a key is the bin's start plus
-// its place in its own chunk plus, for every other chunk of the bin, the number of keys there that come
-// before it: the smaller ones, and for an earlier chunk also the equal ones (chunks follow assignment
-// order, so this keeps the sort stable).  One workgroup per chunk; the other chunks pass through LDS one
-// at a time and are searched by bisection; kMergeSlices workgroups share the keys of one chunk, so that a
-// bin holding most of the input still spreads over the chip.  Leaves at once when no bin has several chunks.
-constexpr int kMergeSlices = 4;  // workgroups that share the keys of one chunk
-constexpr int kMergeOwn = kBinChunk / kMergeSlices / kBinThreads;  // keys per thread: 2
-
-__global__ __launch_bounds__(kBinThreads) void bin_merge_kernel(BinSortArgs a) {
-  __shared__ uint64_t other[kBinChunk];  // 16 KB
-  if (a.bin_start[kGroupBins + 2] == 0) return;   // no bin has several chunks: the usual case
-  // a fixed, small grid walks the (chunk, slice) items: the launch is idle on almost every input, and an idle
-  // launch of one workgroup per item costs 2 us more than this one
-  const uint32_t items = a.bin_start[kGroupBins + 1] * kMergeSlices;
-  for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
-  const uint32_t cidx = item / kMergeSlices, slice = item % kMergeSlices;
-  const uint32_t entry = a.chunk_tbl[cidx];
-  const uint32_t bin = entry >> 16, chunk = entry & 0xffffu;
-  const uint32_t lo_bin = a.bin_start[bin], hi_bin = a.bin_start[bin + 1];
-  if (hi_bin - lo_bin <= (uint32_t)kBinChunk) continue;   // workgroup-uniform
-  const uint32_t chunks = (hi_bin - lo_bin + kBinChunk - 1) / kBinChunk;
-  const uint32_t lo = lo_bin + chunk * kBinChunk, hi = min(lo + (uint32_t)kBinChunk, hi_bin);
-  const uint32_t n = hi - lo;
-  constexpr int kItems = kBinChunk / kBinThreads;  // keys of another chunk a thread stages: 8
-  uint64_t key[kMergeOwn];
-  uint32_t before[kMergeOwn];
-  bool repeat[kMergeOwn];
-#pragma unroll
-  for (int q = 0; q < kMergeOwn; ++q) {
-    const uint32_t i = slice * (kBinChunk / kMergeSlices) + threadIdx.x + q * kBinThreads;
-    key[q] = i < n ? a.key[0][lo + i] : 0;
-    before[q] = i;  // keys before it in its own chunk
-    repeat[q] = i < n && i > 0 && a.key[0][lo + i - 1] == key[q];
-  }
-  // the other chunks pass through LDS one at a time; the next one is fetched into registers while the
-  // current one is searched
-  auto fetch = [&](uint32_t c, uint64_t (&v)[kItems]) {
-    const uint32_t olo = lo_bin + c * kBinChunk, on = min((uint32_t)kBinChunk, hi_bin - olo);
-#pragma unroll
-    for (int q = 0; q < kItems; ++q) {
-      const uint32_t i = threadIdx.x + q * kBinThreads;
-      v[q] = a.key[0][olo + min(i, on - 1)];
-    }
-  };
-  auto next_other = [&](uint32_t c) { return c + 1 == chunk ? c + 2 : c + 1; };
-  uint64_t staged[kItems];
-  uint32_t c = chunk == 0 ? 1u : 0u;
-  fetch(c, staged);
-  for (; c < chunks; c = next_other(c)) {
-    const uint32_t on = min((uint32_t)kBinChunk, hi_bin - (lo_bin + c * kBinChunk));
-    __syncthreads();  // the previous chunk has been searched
-#pragma unroll
-    for (int q = 0; q < kItems; ++q) other[threadIdx.x + q * kBinThreads] = staged[q];
-    __syncthreads();
-    if (next_other(c) < chunks) fetch(next_other(c), staged);
-    const bool earlier = c < chunk;
-    // number of keys of the other chunk that are < key (later chunk) or <= key (earlier chunk): bisection
-    // with a fixed number of steps, the thread's keys side by side so that the LDS reads overlap
-    uint32_t pos[kMergeOwn];
-#pragma unroll
-    for (int q = 0; q < kMergeOwn; ++q) pos[q] = 0;
-    for (uint32_t step = kBinChunk; step >= 1; step >>= 1) {
-#pragma unroll
-      for (int q = 0; q < kMergeOwn; ++q) {
-        const uint32_t t = pos[q] + step;
-        const uint64_t v = other[min(t, on) - 1];
-        const bool take = t <= on && (earlier ? v <= key[q] : v < key[q]);
-        pos[q] = take ? t : pos[q];
-      }
-    }
-#pragma unroll
-    for (int q = 0; q < kMergeOwn; ++q) {
-      before[q] += pos[q];
-      if (earlier && pos[q] > 0 && other[pos[q] - 1] == key[q]) repeat[q] = true;  // an equal key in an earlier chunk
-    }
-  }
-  // the keys land anywhere in the bin: heads are counted per numbering tile in LDS first
-  __syncthreads();
-  uint32_t* tile_cnt = reinterpret_cast<uint32_t*>(other);
-  const uint32_t first_tile = lo_bin >> kSegTileBits, tiles = ((hi_bin - 1) >> kSegTileBits) - first_tile + 1;
-  static_assert(sizeof(other) >= (kFusedMaxTiles * kSortTile / kSegTile) * sizeof(uint32_t), "tile counters fit");
-  for (uint32_t t = threadIdx.x; t < tiles; t += kBinThreads) tile_cnt[t] = 0;
-  __syncthreads();
-#pragma unroll
-  for (int q = 0; q < kMergeOwn; ++q) {
-    const uint32_t i = slice * (kBinChunk / kMergeSlices) + threadIdx.x + q * kBinThreads;
-    if (i < n) {
-      const uint32_t at = lo_bin + before[q];
-      a.key[1][at] = key[q];
-      a.perm[at] = a.idx[0][lo + i];
-      if (!repeat[q]) atomicAdd(&tile_cnt[(at >> kSegTileBits) - first_tile], 1u);
-    }
-  }
-  __syncthreads();
-  for (uint32_t t = threadIdx.x; t < tiles; t += kBinThreads)
-    if (tile_cnt[t] != 0) atomicAdd(&a.tile_heads[first_tile + t], tile_cnt[t]);
-  __syncthreads();   // `other` is free for the next item
-  }
+  if (!alone) merge_up(a, lo_bin, hi_bin, chunk, blockIdx.x - chunk, merge_lds, &cnt[0][0], merge_state);
 }
 
 int bits_for(uint64_t max_value) {  // number of bits needed to hold max_value
@@ -982,12 +1097,12 @@ bool plan_group(int64_t T, int d, int k, int E, int L, int r, GroupPlan* plan) {
   }
   p.off_table = off;
   off = align256(off + (size_t)kGroupBins * p.sort_blocks * 4);
-  p.off_blocksum = off;
-  off = align256(off + ((size_t)p.seg_blocks + 1) * 4);
-  p.off_binstart = off;
-  off = align256(off + ((size_t)kGroupBins + 3) * 4);
-  p.off_chunktbl = off;
   const size_t max_chunks = (size_t)kGroupBins + (size_t)((p.N + kBinChunk - 1) / kBinChunk);  // one per non-empty bin and per kBinChunk keys
+  p.off_blocksum = off;   // head counts per numbering tile (+ 1), then the merge arrival counters: cleared together
+  off = align256(off + ((size_t)p.seg_blocks + 1 + max_chunks) * 4);
+  p.off_binstart = off;
+  off = align256(off + ((size_t)kGroupBins + 2) * 4);
+  p.off_chunktbl = off;
   off = align256(off + max_chunks * 4);
   p.off_chunkheads = off;
   off = align256(off + max_chunks * 16);
@@ -1049,11 +1164,12 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     a.table = table;
     a.bin_start = bin_start;
     a.chunk_tbl = (uint32_t*)(ws + plan.off_chunktbl);
-    // the histogram kernel also clears the per-tile head counts that the bin kernels add to
+    // the histogram kernel also clears the per-tile head counts and the arrival counters that the bin kernel adds to
+    const uint32_t max_chunks = (uint32_t)kGroupBins + (N + kBinChunk - 1) / kBinChunk;
     hipError_t e = hipSuccess;
 #define LSHMOE_GLOBAL_PASS(TILE)                                                                                     \
     LSHMOE_LAUNCH((sort_hist_kernel<true, true, TILE>), grid, block, 0, stream, src, N, a.shift, a.mask, nblk, table, \
-                  blocksum, plan.seg_blocks + 1);                                                                       \
+                  blocksum, plan.seg_blocks + 1 + max_chunks);                                                          \
     e = launch_scatter<true, true, TILE>(src, N, a, keybuf[0], idxbuf[0], stream)
     if (plan.tile == 512) { LSHMOE_GLOBAL_PASS(512); }
     else if (plan.tile == 1024) { LSHMOE_GLOBAL_PASS(1024); }
@@ -1064,7 +1180,7 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     b.bin_start = bin_start;
     b.chunk_tbl = a.chunk_tbl;
     b.key[0] = keybuf[0]; b.key[1] = keybuf[1];
-    b.idx[0] = idxbuf[0];
+    b.idx[0] = idxbuf[0]; b.idx[1] = idxbuf[1];
     b.perm = perm;
     b.passes = plan.low_passes;
     for (int p = 0; p < plan.low_passes; ++p) {
@@ -1076,9 +1192,9 @@ hipError_t launch_group(const GroupPlan& plan, const int32_t* expert, const uint
     b.sub_mask = (1u << sub_bits) - 1u;
     b.tile_heads = blocksum;
     b.chunk_heads = (uint4*)(ws + plan.off_chunkheads);
-    const dim3 chunks((uint32_t)kGroupBins + (N + kBinChunk - 1) / kBinChunk), threads(kBinThreads);
+    b.merge_arrivals = blocksum + plan.seg_blocks + 1;
+    const dim3 chunks(max_chunks), threads(kBinThreads);
     LSHMOE_LAUNCH(bin_sort_kernel, chunks, threads, kBinSortLds, stream, b);
-    LSHMOE_LAUNCH(bin_merge_kernel, dim3(chunks.x * kMergeSlices < 512u ? chunks.x * kMergeSlices : 512u), threads, 0, stream, b);
     // the heads per numbering tile are known: number the clusters (the tile count is within kSelfPrefixMaxTiles here)
     LSHMOE_LAUNCH(seg_write_kernel<true>, dim3(plan.seg_blocks), dim3(kSegThreads), 0, stream,
                        (const uint64_t*)keybuf[1], perm, N, (uint32_t)E, plan.bbits, blocksum, seg_offsets, seg_expert,

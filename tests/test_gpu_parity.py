@@ -132,6 +132,29 @@ def test_group_routes_by_key_width_and_size(H, N, E, L, r):
     H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn, bucket_override=ids, skip_hash=True)
 
 
+@pytest.mark.parametrize("N,bins_used,distinct", [
+    (4100, 1, 3), (6149, 1, 4000), (10240, 1, 7), (34817, 1, 20000), (65536, 1, 1), (131072, 1, 90000),
+    (524288, 1, 300000), (524288, 1, 2), (70001, 3, 50000), (200003, 5, 11), (300000, 2, 150000), (40000, 7, 64)])
+def test_group_bins_of_many_chunks(H, N, bins_used, distinct):
+    # Bins of the one global pass that hold 2 .. 256 chunks of 2048 keys (all keys share the top key bits of a few
+    # bins): the chunks are merged pairwise by the workgroups that sorted them, level by level; odd chunk counts,
+    # a ragged last chunk, runs without a neighbour, many equal keys and all-distinct keys.
+    d, dtype, E, L, r = 8, "bf16", 4, 4, 16                     # 2 expert bits + 20 bucket bits: top 9 bits pick the bin
+    rng = np.random.default_rng(N + 7 * bins_used + distinct)
+    tokens = synth.f32_to_storage(rng.standard_normal((N, d)).astype(np.float32), dtype)
+    rot = synth.f32_to_storage(rng.standard_normal((L, r, d)).astype(np.float32), dtype)
+    low_bits = 20 - 7                                            # key bits below the bin digit
+    tops = rng.choice(4 << 7, bins_used, replace=False)          # (expert, top 7 bucket bits) of the bins used
+    pool_top = tops[rng.integers(0, bins_used, distinct)]
+    pool_low = rng.integers(0, 1 << low_bits, distinct, dtype=np.uint64)
+    pick = rng.integers(0, distinct, N)
+    top = pool_top[pick]
+    expert = (top >> 7).astype(np.int32).reshape(N, 1)
+    ids = ((top & 127).astype(np.uint64) << np.uint64(low_bits)) | pool_low[pick]
+    print("case many chunks N", N, "bins", bins_used, "distinct keys", distinct, flush=True)
+    H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn, bucket_override=ids, skip_hash=True)
+
+
 def test_large_inputs_take_the_histogram_scan_scatter_route(H):
     # more than 256 sort tiles: per-pass histogram + table scan + scatter kernels
     tokens, rot, expert = _rand_inputs(41, 280000, 8, 2, 3, 2, 4, "bf16", centers=5000)

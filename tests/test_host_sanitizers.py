@@ -27,9 +27,8 @@ def test_abi_error_paths_are_clean_under_asan_and_ubsan(tmp_path):
         assert res.returncode == 0, res.stderr
         objs.append(obj)
     exe = str(tmp_path / "abi_errors_san")
-    res = subprocess.run([build.HIPCC, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined",
-                          "-fno-gpu-sanitize", *objs, *[os.path.join(build.BUILD_DIR, o + ".o") for o in others], "-o", exe],
-                         capture_output=True, text=True, timeout=600)
+    link = [build.HIPCC, "--offload-arch=gfx950", *san, *objs, *[os.path.join(build.BUILD_DIR, o + ".o") for o in others], "-o", exe]
+    res = subprocess.run(link, capture_output=True, text=True, timeout=600)
     assert res.returncode == 0, res.stderr
     res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert res.returncode == 0, res.stdout + res.stderr
