@@ -753,11 +753,12 @@ __device__ __forceinline__ void merge_runs(const uint64_t* src_key, const int32_
     if (count_heads && t > 0 && threadIdx.x < (uint32_t)kChunkTiles && st.tile_cnt[(t - 1) & 1][threadIdx.x] != 0)
       atomicAdd(&tile_heads[((lo_a + out0 - kBinChunk) >> kSegTileBits) + threadIdx.x], st.tile_cnt[(t - 1) & 1][threadIdx.x]);
     {
-      // Every thread produces kItems consecutive outputs of the tile: one bisection along the merge path finds how
+      // Every thread produces kItems consecutive outputs of the tile: one search along the merge path finds how
       // many of the outputs before its first one come from the left part, then it merges step by step (on equal
       // keys the left part goes first).  A wave runs alone on its SIMD here, so instructions per key are what
       // counts: ranking every key by a bisection of its own took eight times as many.
       const uint32_t diag = min(threadIdx.x * (uint32_t)kItems, cn);
+      // (plain bisection: in LDS a probe is cheap and the sixteen-way search's extra instructions cost more)
       uint32_t lo = diag > cb ? diag - cb : 0u, hi = min(diag, ca);
       while (lo < hi) {
         const uint32_t mid = (lo + hi) >> 1;   // mid < ca; diag - 1 - mid in [0, cb)
