@@ -101,6 +101,7 @@ def measured_peaks():
     lib.peaks_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
     lib.peaks_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
     lib.peaks_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.peaks_mfma_bf16_random.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     stream = torch.cuda.current_stream().cuda_stream
     nbytes = 2 << 30
     src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
@@ -125,10 +126,16 @@ def measured_peaks():
     t_read = best(lambda: lib.peaks_read(src.data_ptr(), nbytes, sink.data_ptr(), 8192, stream))
     t_copy = best(lambda: lib.peaks_copy(src.data_ptr(), dst.data_ptr(), nbytes, 8192, stream))
     t_mfma = best(lambda: lib.peaks_mfma_bf16(blocks, iters, mout.data_ptr(), stream))
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    operands = torch.randn(16 * 64 * 8, generator=gen, device="cuda").to(torch.bfloat16)
+    t_mfma_r = best(lambda: lib.peaks_mfma_bf16_random(operands.data_ptr(), blocks, iters, mout.data_ptr(), stream))
     return {"hbm_read_gbs": nbytes / (t_read * 1e-3) / 1e9,
             "hbm_copy_gbs": 2 * nbytes / (t_copy * 1e-3) / 1e9,      # bytes read plus bytes written
             "mfma_bf16_tflops": blocks * 4 * iters * 4 * 32768 / (t_mfma * 1e-3) / 1e12,
-            "note": "2 GiB streaming read / copy (read + written bytes) by 8192 workgroups, %d x 4 waves x %d x 4 MFMA 32x32x16 bf16" % (blocks, iters)}
+            "mfma_bf16_random_operands_tflops": blocks * 4 * iters * 4 * 32768 / (t_mfma_r * 1e-3) / 1e12,
+            "note": "2 GiB streaming read / copy (read + written bytes) by 8192 workgroups, %d x 4 waves x %d x 4 MFMA "
+                    "32x32x16 bf16, once on constant operands and once on eight changing pairs of Gaussian ones (the "
+                    "matrix cores clock lower on those)" % (blocks, iters)}
 
 
 def main():
@@ -481,6 +488,8 @@ def main():
         result["roofline"]["frac_of_measured_copy_rate"] = (traffic if traffic else restore_bytes) / (dec_ms * 1e-3) / 1e9 / mp["hbm_copy_gbs"]
         if cfg.dtype == "bf16":
             result["hash_mfma"]["frac_of_measured_mfma_rate"] = result["hash_mfma"]["tflops"] / mp["mfma_bf16_tflops"]
+            result["hash_mfma"]["frac_of_measured_mfma_rate_random_operands"] = (
+                result["hash_mfma"]["tflops"] / mp["mfma_bf16_random_operands_tflops"])
     result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample) if args.cpu_sample >= 0 else None
     print(json.dumps(result))
 

@@ -69,6 +69,37 @@ __global__ __launch_bounds__(256) void mfma_kernel(float* out, int iters) {
   out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The same loop on operands that differ from one MFMA to the next: eight fragment pairs of random bf16 values of
+// magnitude about one, read once from `operands` (64 lanes x 16 pieces of 16 bytes per workgroup wave, the same for
+// every wave) and cycled through.  The matrix cores draw more power on such data than on constants, and the
+// clock they sustain is lower: this is the rate a GEMM on real data can hope for.
+__global__ __launch_bounds__(256) void mfma_random_kernel(const uint4* __restrict__ operands, float* out, int iters) {
+  floatx16 acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[t][j] = 0.0f;
+  const int lane = threadIdx.x & 63;
+  bf16x8 a[8], b[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    a[q] = __builtin_bit_cast(bf16x8, operands[(2 * q) * 64 + lane]);
+    b[q] = __builtin_bit_cast(bf16x8, operands[(2 * q + 1) * 64 + lane]);
+  }
+  for (int i = 0; i < iters; i += 2) {   // two rounds per pass: every MFMA of a pass has operands of its own
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[4 * r + t], b[4 * r + t], acc[t], 0, 0, 0);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s += acc[t][j];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -94,6 +125,15 @@ int peaks_copy(const void* src, void* dst, size_t bytes, int blocks, void* strea
 int peaks_mfma_bf16(int blocks, int iters, float* out, void* stream) {
   if (out == nullptr || blocks <= 0 || iters <= 0) return (int)hipErrorInvalidValue;
   hipLaunchKernelGGL(mfma_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, iters);
+  return (int)hipGetLastError();
+}
+
+// The same count of MFMAs on changing operands.  operands: 16 x 64 pieces of 16 bytes (16 KB) of device memory
+// holding bf16 values; iters must be even.
+int peaks_mfma_bf16_random(const void* operands, int blocks, int iters, float* out, void* stream) {
+  if (operands == nullptr || out == nullptr || blocks <= 0 || iters <= 0 || iters % 2 != 0) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(mfma_random_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)operands, out,
+                     iters);
   return (int)hipGetLastError();
 }
 
