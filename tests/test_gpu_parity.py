@@ -155,6 +155,36 @@ def test_group_bins_of_many_chunks(H, N, bins_used, distinct):
     H.run_and_check(tokens, rot, expert, E, dtype, _scale_fn, bucket_override=ids, skip_hash=True)
 
 
+def test_chunk_merges_give_the_same_result_every_time(H):
+    # The merges inside the bin-sort launch depend on which of two neighbouring workgroups finishes last; the result
+    # must not.  One bin of 64 chunks and three bins of a dozen, forty calls on the same buffers (workspace included),
+    # every output compared with the first call's (which the parity cases above compare with the oracle).
+    lsh = H.lsh
+    E, L, r, d, N = 4, 4, 16, 8, 131072
+    rng = np.random.default_rng(99)
+    for bins_used in (1, 3):
+        tops = rng.choice(4 << 7, bins_used, replace=False)
+        top = tops[rng.integers(0, bins_used, N)]
+        expert = torch.tensor((top >> 7).astype(np.int32).reshape(N, 1), device="cuda")
+        ids = torch.tensor((((top & 127).astype(np.uint64) << np.uint64(13)) |
+                            rng.integers(0, 1 << 13, N, dtype=np.uint64)).astype(np.int64), device="cuda")
+        x = torch.randn((N, d), device="cuda").to(torch.bfloat16)
+        out = lsh.CompressOutputs.allocate(N, d, 1, E, L, r, torch.bfloat16)
+        first = None
+        for call in range(40):
+            lsh.lshmoe_compress(x, expert, ids, E, L, r, out)
+            torch.cuda.synchronize()
+            S = int(out.num_segments.item())
+            got = (S, out.perm.clone(), out.seg_of.clone(), out.seg_offsets[:S + 1].clone(), out.seg_expert[:S].clone(),
+                   out.centroids[:S].clone())
+            if first is None:
+                first = got
+                continue
+            assert got[0] == first[0], "call %d: cluster count differs" % call
+            for a, b in zip(got[1:], first[1:]):
+                assert torch.equal(a, b), "call %d differs from the first call" % call
+
+
 def test_large_inputs_take_the_histogram_scan_scatter_route(H):
     # more than 256 sort tiles: per-pass histogram + table scan + scatter kernels
     tokens, rot, expert = _rand_inputs(41, 280000, 8, 2, 3, 2, 4, "bf16", centers=5000)
