@@ -83,11 +83,14 @@ def cpu_baseline(w, sample_tokens: int):
     }
 
 
-def event_stride(steps: int) -> int:
-    """Steps between two steps whose stages are timed with events: an event record costs about 3 us of stream time
-    (4 records: 13 us on a 250 us step), so long runs sample every 8th step; short runs sample more densely so that
-    any run of 10 steps or more still yields 8 or more intervals per stage."""
-    return max(1, min(8, steps // 10))
+def event_window(steps: int):
+    """(first, count): the run of consecutive steps of the timed region whose stages are timed with events.  An event
+    record costs 3 to 5 us of stream time, so the records are kept few: the steps of the window follow one another, so
+    that the event after a step's decompress call is also the one before the next step's hash call (3 records per
+    step and one more, instead of 4 per step), and the window holds 8 steps (16 from 100 steps on), in the middle of
+    the run: any run of 8 steps or more yields 8 or more intervals per stage."""
+    count = min(steps, 8 if steps < 100 else 16)
+    return (steps - count) // 2, count
 
 
 def measured_peaks():
@@ -207,10 +210,10 @@ def main():
     seg_len = np.diff(outs[0].seg_offsets[:S + 1].cpu().numpy())
     n_single = int((seg_len == 1).sum())
 
-    def step(i, ev=None):
+    def step(i, ev=None, first_of_window=True):
         c = i % copies
         x, o = xs[c], outs[c]
-        if ev: ev[0].record()
+        if ev and first_of_window: ev[0].record()   # otherwise ev[0] is the previous step's ev[3], already recorded
         lsh.lshmoe_hash(x, rot, bucket)
         if ev: ev[1].record()
         lsh.lshmoe_compress(x, expert, bucket, E, L, r, o)
@@ -233,15 +236,16 @@ def main():
     torch.cuda.synchronize()
 
     K = args.steps
-    # Per-stage durations come from events on the launch stream inside the timed region.  An event record costs
-    # about 3 us of stream time, so only every stride-th step carries them (see event_stride).
-    stride = event_stride(K)
-    sampled = [i for i in range(K) if i % stride == 0]
-    events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(4)] for i in sampled}
+    # Per-stage durations come from events on the launch stream inside the timed region, on a window of consecutive
+    # steps that share their boundary events (see event_window).
+    win_first, win_count = event_window(K)
+    sampled = list(range(win_first, win_first + win_count))
+    chain = [torch.cuda.Event(enable_timing=True) for _ in range(3 * win_count + 1)]
+    events = {win_first + j: chain[3 * j:3 * j + 4] for j in range(win_count)}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        step(i, events.get(i))
+        step(i, events.get(i), i == win_first)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -267,7 +271,8 @@ def main():
         "config": {"workload": "%s: T=%d d=%d k=%d E=%d L=%d r=%d, Gaussian mixture of %d centers, gate=%s" %
                                (cfg.name, T, d, k, E, L, r, cfg.centers, cfg.gate),
                    "tokens": T, "assignments": N, "segments": S, "compression_rate": S / N,
-                   "single_member_segments": n_single, "input_copies_rotated": copies, "stage_events_every": stride, "stage_event_samples": len(sampled)},
+                   "single_member_segments": n_single, "input_copies_rotated": copies, "stage_event_samples": len(sampled),
+                   "stage_event_steps": "%d consecutive steps from step %d; %d event records" % (win_count, win_first, len(chain))},
         "roofline": {"kernel": "restore_kernel (lshmoe_decompress)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.gate)),
