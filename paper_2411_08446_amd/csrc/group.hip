@@ -28,6 +28,7 @@
 // table with global atomics from inside the scatter was measured slower than
 // the separate histogram launch: device-scope atomics cost ~8 us per pass.)
 #include <atomic>
+#include <cstddef>
 
 #include "kernels.h"
 
@@ -804,6 +805,91 @@ __device__ __forceinline__ void merge_runs(const uint64_t* src_key, const int32_
     atomicAdd(&tile_heads[((lo_a + (tiles - 1) * kBinChunk) >> kSegTileBits) + threadIdx.x], st.tile_cnt[(tiles - 1) & 1][threadIdx.x]);
 }
 
+// The first level of the tree merges two chunks: at most 2 kBinChunk keys, which fit in the merge's LDS block at once
+// (its input and output halves side by side).  No tile boundaries to search in memory, one trip for the inputs, and
+// every thread merges 2 kBinChunk / kBinThreads consecutive outputs: half the time of merge_runs on the same pair,
+// and bins of two chunks are the commonest case of a bin of several.  Same arguments as merge_runs.
+__device__ __forceinline__ void merge_pair(const uint64_t* src_key, const int32_t* src_idx, uint64_t* dst_key, int32_t* dst_idx,
+                                           uint32_t lo_a, uint32_t na, uint32_t nb, bool count_heads, uint32_t* tile_heads,
+                                           MergeLds& m, MergeState& st) {
+  constexpr int kItems = 2 * kBinChunk / kBinThreads;   // 16
+  constexpr uint32_t kLast = 2 * kBinChunk - 1;
+  static_assert(offsetof(MergeLds, out_key) == sizeof(uint64_t) * kBinChunk &&
+                    offsetof(MergeLds, out_idx) == offsetof(MergeLds, in_idx) + sizeof(int32_t) * kBinChunk,
+                "the two halves of the key and of the id arrays are adjacent");
+  uint64_t* K = m.in_key;   // [2 kBinChunk]
+  int32_t* I = m.in_idx;    // [2 kBinChunk]
+  uint32_t* heads = &st.tile_cnt[0][0];   // 2 kBinChunk positions touch at most 2 kBinChunk / kSegTile + 1 numbering tiles
+  static_assert(2 * kBinChunk / kSegTile + 1 <= 2 * kChunkTiles, "head counters of a pair fit the merge state");
+  const uint32_t n = na + nb;   // <= 2 kBinChunk
+  __syncthreads();   // LDS of the chunk sort is no longer read
+  {
+    uint64_t pk[kItems];
+    int32_t pi[kItems];
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+      const uint32_t e = min(threadIdx.x + q * kBinThreads, n - 1);
+      pk[q] = src_key[lo_a + e];
+      pi[q] = src_idx[lo_a + e];
+    }
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+      const uint32_t e = threadIdx.x + q * kBinThreads;
+      if (e < n) {
+        K[merge_slot(e)] = pk[q];
+        I[e] = pi[q];
+      }
+    }
+  }
+  if (threadIdx.x < 2u * kChunkTiles) heads[threadIdx.x] = 0;
+  lds_barrier();
+  uint64_t ok[kItems];
+  int32_t oi[kItems];
+  const uint32_t diag = min(threadIdx.x * (uint32_t)kItems, n);
+  {
+    uint32_t lo = diag > nb ? diag - nb : 0u, hi = min(diag, na);
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi) >> 1;   // mid < na; diag - 1 - mid in [0, nb)
+      if (K[merge_slot(mid)] <= K[merge_slot(na + diag - 1 - mid)]) lo = mid + 1; else hi = mid;
+    }
+    uint32_t ai = lo, bi = na + (diag - lo);   // next element of either run, as indices into K
+    uint64_t ka = K[merge_slot(min(ai, kLast))], kb = K[merge_slot(min(bi, kLast))];
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+      const bool take_a = ai < na && (bi >= n || ka <= kb);
+      ok[q] = take_a ? ka : kb;
+      oi[q] = I[min(take_a ? ai : bi, kLast)];
+      if (take_a) { ++ai; ka = K[merge_slot(min(ai, kLast))]; }
+      else { ++bi; kb = K[merge_slot(min(bi, kLast))]; }
+    }
+  }
+  lds_barrier();   // every thread has read its inputs: the block now takes the outputs, in order
+#pragma unroll
+  for (int q = 0; q < kItems; ++q) {
+    const uint32_t at = diag + q;
+    if (at < n) {
+      K[at] = ok[q];
+      I[at] = oi[q];
+    }
+  }
+  lds_barrier();
+  const uint32_t first_tile = lo_a >> kSegTileBits;
+#pragma unroll
+  for (int q = 0; q < kItems; ++q) {
+    const uint32_t e = threadIdx.x + q * kBinThreads;
+    if (e < n) {
+      const uint64_t key = K[e];
+      dst_key[lo_a + e] = key;
+      dst_idx[lo_a + e] = I[e];
+      // counted only at the root, whose first key is the bin's first and always starts a cluster
+      if (count_heads && (e == 0 || K[e - 1] != key)) atomicAdd(&heads[((lo_a + e) >> kSegTileBits) - first_tile], 1u);
+    }
+  }
+  __syncthreads();
+  if (count_heads && threadIdx.x < 2u * kChunkTiles && heads[threadIdx.x] != 0)
+    atomicAdd(&tile_heads[first_tile + threadIdx.x], heads[threadIdx.x]);
+}
+
 // Called by every thread of a workgroup that has just written chunk `chunk` of a bin of several chunks, sorted,
 // into buffer `start_buf`.  Returns when the workgroup has nothing left to merge.
 __device__ __forceinline__ void merge_up(const BinSortArgs& a, uint32_t lo_bin, uint32_t hi_bin, uint32_t chunk, uint32_t first_chunk_slot,
@@ -838,7 +924,10 @@ __device__ __forceinline__ void merge_up(const BinSortArgs& a, uint32_t lo_bin, 
     __threadfence();      // second to arrive: the other run is complete and visible
     const uint32_t na = (right0 - left0) * kBinChunk;             // a left-hand run is always full
     const uint32_t end = min(lo_bin + (left0 + (1u << j)) * kBinChunk, hi_bin);
-    merge_runs(src_key, src_idx, dst_key, dst_idx, lo_a, na, end - lo_a - na, final_level, a.tile_heads, m, split, st);
+    if (j == 1)
+      merge_pair(src_key, src_idx, dst_key, dst_idx, lo_a, na, end - lo_a - na, final_level, a.tile_heads, m, st);
+    else
+      merge_runs(src_key, src_idx, dst_key, dst_idx, lo_a, na, end - lo_a - na, final_level, a.tile_heads, m, split, st);
   }
 }
 
