@@ -469,6 +469,11 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
   static_assert((DX == DR + 1 || DX == DR) && DR >= 1, "the wait below assumes the tokens run as far ahead as R or one chunk further");
   // loads issued after those of chunk c + 1, at the end of iteration c (iteration i issues R chunk i + DR, then token chunk i + DX)
   constexpr int kAllowed = (DR - 1) * (LR + LX) + (DX == DR + 1 ? LX : 0);
+  // The token loads of an iteration come from HBM; a wave that issues them in one burst sits in the issue stage
+  // while the memory pipeline is full, its MFMAs waiting behind it.  With two halves (the largest shapes) they are
+  // issued a quarter at a time behind the MFMAs of each k step instead; the order of a wave's loads stays R, then
+  // tokens, so the wait at the end of the iteration counts as before.
+  constexpr bool kSpreadX = HALVES == 2 && DX == DR + 1 && LX >= kSteps;
   extern __shared__ uint4 lds[];             // R ring [DR + 1][kSlotsR], then token ring [DX + 1][kSlotsX]
   const int tid = threadIdx.x;
   __builtin_assume(tid >= 0 && tid < TH);
@@ -524,6 +529,13 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
 #pragma unroll
       for (int i = 0; i < LR; ++i) load16_to_lds(arow[i] + (size_t)chunk * (kPieces * 16), dst + 8 * i * kPieces);
     };
+    // part s of a token chunk's loads: a quarter of them per k step when the loads are spread over the chunk's steps
+    auto stage_x_part = [&](int chunk, int part) {
+      uint4* dst = lds_x + (chunk % (DX + 1)) * S::kSlotsX + (8 * wv * LX) * kPieces;
+#pragma unroll
+      for (int i = 0; i < LX; ++i)
+        if (i * kSteps / LX == part) load16_to_lds(x_blk + (size_t)chunk * (kPieces * 16) + off_x[i], dst + 8 * i * kPieces);
+    };
     auto stage_x = [&](int chunk) {
       uint4* dst = lds_x + (chunk % (DX + 1)) * S::kSlotsX + (8 * wv * LX) * kPieces;
 #pragma unroll
@@ -550,7 +562,8 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
     for (int c = 0; c < nchunks; ++c) {
       // ring slots written now were last read in chunk c - 1, whose closing barrier every wave has passed
       if (c + DR < nchunks) stage_r(c + DR);
-      if (c + DX < nchunks) stage_x(c + DX);
+      const bool more_x = c + DX < nchunks;
+      if (!kSpreadX && more_x) stage_x(c + DX);
       const uint4* bufa = lds + (c % (DR + 1)) * S::kSlotsR;
       const uint4* bufb = lds_x + (c % (DX + 1)) * S::kSlotsX;
       uint4 fa[2][MTW], fb[2][NTW];          // fragments of the step in flight and of the next one
@@ -572,6 +585,7 @@ __global__ __launch_bounds__(GROUPS * HALVES * 64, 1) void hash_stream_kernel(
 #pragma unroll
           for (int u = 0; u < NTW; ++u) Mma<DT>::run(fa[s & 1][t], fb[s & 1][u], acc[t][u]);
         __builtin_amdgcn_sched_barrier(0);
+        if (kSpreadX && more_x) stage_x_part(c + DX, s);   // behind the step's MFMAs, which are queued by now
       }
       // chunk c + 1 must have landed: everything but the loads issued after it (none of them near the end)
       if (c + DX < nchunks) wait_vm_at_most<kAllowed>(); else wait_vm_at_most<0>();
