@@ -645,10 +645,11 @@ constexpr size_t kBinSortLds = 2 * (size_t)kBinChunk * (8 + 4);  // two (key, id
 // that every run of a level sits in the same one of the two buffers and a merge never writes where it reads; the
 // chunk sort starts in the buffer from which the root's output lands in the final arrays.  The merge is stable
 // (on equal keys the left run, i.e. the lower assignment ids, goes first) and proceeds in tiles of kBinChunk
-// outputs: the tile's share of either run is found by bisection along the merge path (all boundaries at once, one
-// per thread), staged in LDS, ranked there by bisection, and written out in order.  The root also counts the
-// cluster heads per numbering tile.  Depth is log2 of the bin's chunk count, so one bin that holds the whole input
-// still takes about as long as the separate merge launch this replaces, which was idle on almost every input.
+// outputs: the tile's share of either run is found by a search along the merge path (all boundaries at once, one
+// per thread), staged in LDS, merged there (every thread a run of consecutive outputs) and written out in order.
+// The root also counts the cluster heads per numbering tile.  Depth is log2 of the bin's chunk count; a node is one
+// workgroup, so bins of several chunks take about twice as long as with the separate merge launch this replaces
+// (four workgroups per chunk) - which every other input paid for with an idle launch.
 struct MergeLds {
   uint64_t in_key[kBinChunk];    // the tile's share of the left run, then of the right run
   uint64_t out_key[kBinChunk];
@@ -691,8 +692,8 @@ __device__ __forceinline__ uint32_t merge_path_split(const uint64_t* A, uint32_t
 }
 
 // Slot of element i of a staged tile.  The bisection below probes indices that differ by multiples of a power of
-// two; stored plainly those all fall into the same LDS bank (up to 64 lanes one after the other, which made the
-// ranking 8 us per tile); swapping the low five index bits around by the next ten spreads them.
+// two; stored plainly those all fall into the same LDS bank (up to 64 lanes one after the other); swapping the low
+// five index bits around by the next ten spreads them.
 __device__ __forceinline__ uint32_t merge_slot(uint32_t i) { return i ^ ((i >> 5) & 31u) ^ ((i >> 10) & 31u); }
 static_assert(kBinChunk <= (1 << 15), "merge_slot permutes indices below 2^15 inside blocks of 32");
 
