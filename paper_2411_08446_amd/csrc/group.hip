@@ -725,15 +725,14 @@ __device__ __forceinline__ void merge_runs(const uint64_t* src_key, const int32_
   int32_t pi[kItems];
   auto fetch = [&](uint32_t t) {
     const uint32_t a0 = split[t], a1 = split[t + 1];
-    const uint32_t out0 = t * kBinChunk, out1 = min(out0 + (uint32_t)kBinChunk, n);
-    const uint32_t b0 = out0 - a0, ca = a1 - a0, cn = out1 - out0;
+    const uint32_t out0 = t * kBinChunk;
+    const uint32_t b0 = out0 - a0, ca = a1 - a0;
 #pragma unroll
     for (int q = 0; q < kItems; ++q) {
-      const uint32_t e = threadIdx.x + q * kBinThreads;
-      const uint32_t from = min(e < ca ? lo_a + a0 + e : lo_a + na + b0 + (e - ca), lo_a + n - 1);  // e >= cn: unused
+      const uint32_t e = threadIdx.x + q * kBinThreads;   // past the tile's last element: clamped, never used
+      const uint32_t from = min(e < ca ? lo_a + a0 + e : lo_a + na + b0 + (e - ca), lo_a + n - 1);
       pk[q] = src_key[from];
       pi[q] = src_idx[from];
-      (void)cn;
     }
   };
   fetch(0);
